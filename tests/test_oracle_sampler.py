@@ -1,0 +1,208 @@
+"""Pins of the oracle's sampling loop: schedule rules on scripted models, solver
+closed forms, tau=0 => plain sampling, tau=inf => fixed pattern (no GPU)."""
+import numpy as np
+import pytest
+
+import speca_inputs as si
+from oracle import dit, sampler, speca_core as core
+from oracle.sampler import KIND_FULL, KIND_SPEC, KIND_REJECT
+
+
+class ScriptedModel:
+    """Two one-slot blocks whose branch output depends only on the conditioning
+    timestep: F(t) = script(t) * ones.  Hidden state = x; gates = 1; output = 0.
+    Lets a test dictate the verification error at every step."""
+
+    class _S:
+        num_classes = 10
+
+    def __init__(self, script):
+        self.script = script
+        self.n_blocks, self.slots_per_block, self.n_slots = 2, [1, 1], 2
+        self.s = self._S()
+        self.calls = []
+
+    def begin(self, x, t, labels):
+        return np.zeros((len(labels), 1, 4)), t
+
+    def block_real(self, l, h, c):
+        self.calls.append(("real", l, c))
+        f = np.full_like(h, self.script(c))
+        return h + f, [f]
+
+    def block_fold(self, l, h, c, feats):
+        return h + feats[0]
+
+    def finish(self, h, c):
+        return np.zeros((h.shape[0], 1, 2, 2))
+
+    def forward(self, x, t, labels):
+        h, c = self.begin(x, t, labels)
+        feats = []
+        for l in range(2):
+            h, f = self.block_real(l, h, c)
+            feats += f
+        self.calls.append(("full", c))
+        return self.finish(h, c), feats
+
+
+def _solver(S):
+    return sampler.Solver("flow", np.arange(S, dtype=np.float32), np.linspace(1, 0, S + 1).astype(np.float32))
+
+
+def _run(script, S, tau, **cfg):
+    m = ScriptedModel(script)
+    out, tr = sampler.sample(m, sampler.SpecaConfig(**cfg), _solver(S), np.asarray(tau, np.float32),
+                             np.zeros((1, 1, 2, 2)), [0])
+    return m, tr
+
+
+def test_infinite_threshold_gives_fixed_pattern():
+    # linear feature: forecast exact from the second reference on; everything is accepted
+    m, tr = _run(lambda t: 2.0 + 0.5 * t, 13, [np.inf] * 13, order=1, interval=4)
+    exp = [KIND_FULL if s % 4 == 0 else KIND_SPEC for s in range(13)]
+    assert tr.kind[0].tolist() == exp
+    assert np.nanmax(tr.err[0, 5:]) < 1e-6          # order-1 forecast of a linear feature is exact
+    # first window has one reference only: order 0 reuse, error = |F(0)-F(k)|/F(k)
+    assert tr.err[0, 2, 0] == pytest.approx(abs(2.0 - 3.0) / 3.0, rel=1e-6)
+
+
+def test_zero_threshold_never_speculates():
+    m, tr = _run(lambda t: 1.0, 9, [0.0] * 9, order=2, interval=3)
+    assert tr.kind[0].tolist() == [KIND_FULL] * 9
+    assert np.all(np.isnan(tr.err))
+    assert sum(1 for c in m.calls if c[0] == "full") == 9
+    assert sum(1 for c in m.calls if c[0] == "real") == 18        # only the full forwards ran blocks
+
+
+def test_rejection_falls_back_and_rebases():
+    # constant feature with a jump at t=6: reuse is exact until the jump, rejected there
+    script = lambda t: 1.0 if t < 6 else 3.0
+    m, tr = _run(script, 12, [0.1] * 12, order=0, interval=5)
+    k = tr.kind[0].tolist()
+    # full at 0; 1..4 accepted; 5 forced (5-0 >= N); 6 rejected -> full, new reference; 7..10 accepted; 11 forced
+    assert k == [0, 1, 1, 1, 1, 0, 2, 1, 1, 1, 1, 0]
+    assert tr.err[0, 6, 0] == pytest.approx(2.0 / 3.0, rel=1e-6)
+    assert tr.err[0, 7, 0] == 0.0
+    # the rejected step ran the verify block and then a full forward
+    full_ts = [c[1] for c in m.calls if c[0] == "full"]
+    assert full_ts == [0.0, 5.0, 6.0, 11.0]
+
+
+def test_accept_is_inclusive_and_uses_step_threshold():
+    # reuse error at step s is |1 - (1+0.1 s)|/(1+0.1 s)
+    script = lambda t: 1.0 + 0.1 * t
+    e = lambda s: np.float32(np.float32(0.1 * s) / np.float32(1 + 0.1 * s))
+    S = 4
+    errs = [core.relative_error_f32(np.full(4, 1.0), np.full(4, script(float(s)))) for s in range(S)]
+    tau = [1.0, float(errs[1]), float(np.nextafter(errs[2], np.float32(0))), 1.0]
+    m, tr = _run(script, S, tau, order=0, interval=10)
+    # step 1: e == tau -> accepted; step 2: e just above tau -> rejected, becomes reference; step 3: vs new reference
+    assert tr.kind[0].tolist() == [0, 1, 2, 1]
+    assert tr.err[0, 3, 0] == pytest.approx(0.1 / 1.3, rel=1e-5)
+
+
+def test_warmup_full_steps():
+    _, tr = _run(lambda t: 1.0, 8, [1.0] * 8, order=1, interval=4, warmup_full=3)
+    assert tr.kind[0].tolist() == [0, 0, 0, 1, 1, 1, 0, 1]
+
+
+def test_accepted_steps_do_not_touch_cache():
+    # quadratic feature, order 1: if an accepted step refreshed the cache the later errors would change
+    script = lambda t: 1.0 + 0.01 * t * t
+    _, tr = _run(script, 7, [np.inf] * 7, order=1, interval=100, warmup_full=2)
+    # references stay at steps 0 and 1: forecast(s) = F(1) + (s-1)(F(1)-F(0))
+    for s in range(2, 7):
+        pred = script(1) + (s - 1) * (script(1) - script(0))
+        assert tr.err[0, s, 0] == pytest.approx(abs(pred - script(s)) / script(s), rel=1e-5)
+
+
+def test_cfg_pair_accepts_only_if_both_rows_pass():
+    class PairModel(ScriptedModel):
+        def block_real(self, l, h, c):
+            f = np.zeros_like(h)
+            f[0] = 1.0                                    # conditional row: constant -> e = 0
+            f[1] = 1.0 if c < 2 else 2.0                  # unconditional row jumps at t=2
+            return h + f, [f]
+    m = PairModel(None)
+    sol = _solver(4); sol.cfg_scale = 1.5
+    out, tr = sampler.sample(m, sampler.SpecaConfig(order=0, interval=10), sol, np.full(4, 0.1, np.float32),
+                             np.zeros((1, 1, 2, 2)), [0])
+    assert tr.kind[0].tolist() == [0, 1, 2, 1]
+    assert tr.err[0, 2, 0] == 0.0 and tr.err[0, 2, 1] == pytest.approx(0.5)
+
+
+# --- solvers -----------------------------------------------------------------------------
+
+
+def test_ddim_closed_forms():
+    x = np.array([2.0, -1.0])
+    # zero predicted noise: pure rescale by sqrt(abar_prev/abar_t)
+    np.testing.assert_allclose(sampler.ddim_update(x, 0 * x, 0.25, 1.0), x / 0.5)
+    # x = sqrt(a) x0 + sqrt(1-a) eps with the true eps: lands on the same (x0, eps) at the next level
+    x0, eps = np.array([0.3, -0.7]), np.array([1.1, 0.4])
+    a, b = 0.36, 0.81
+    xt = np.sqrt(a) * x0 + np.sqrt(1 - a) * eps
+    np.testing.assert_allclose(sampler.ddim_update(xt, eps, a, b), np.sqrt(b) * x0 + np.sqrt(1 - b) * eps, rtol=1e-12)
+    np.testing.assert_allclose(sampler.ddim_update(xt, eps, a, 1.0), x0, rtol=1e-12)
+
+
+def test_flow_and_cfg_closed_forms():
+    ts, sig = si.flow_tables(10)
+    x = np.array([1.0, 2.0]); v = np.array([0.5, -1.0])
+    for s in range(10):
+        x = sampler.euler_flow_update(x, v, float(sig[s]), float(sig[s + 1]))
+    np.testing.assert_allclose(x, np.array([1.0, 2.0]) - v, rtol=1e-6)      # sigma runs 1 -> 0
+    assert sampler.cfg_combine(3.0, 1.0, 1.5) == 4.0 and sampler.cfg_combine(3.0, 1.0, 1.0) == 3.0
+
+
+def test_ddim_tables():
+    ts, ab = si.ddim_tables(50)
+    assert ts[0] == 980 and ts[-1] == 0 and len(ab) == 51 and ab[-1] == 1.0
+    assert np.all(np.diff(ab) > 0) and ab[-2] == pytest.approx(1 - 1e-4)
+
+
+# --- tiny DiT, configuration 1 --------------------------------------------------------------
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    s = si.dit_tiny()
+    m = dit.DiTOracle(s, si.make_dit_weights(s, 0))
+    ts, ab = si.ddim_tables(20)
+    return s, m, sampler.Solver("ddim", ts, ab), si.make_latents(2, 4, 8, 0), si.make_labels(2, s.num_classes, 0)
+
+
+def test_tiny_dit_tau_zero_is_plain_sampling(tiny):
+    s, m, sol, lat, lab = tiny
+    plain = sampler.sample_plain(m, sol, lat, lab)
+    out, tr = sampler.sample(m, sampler.SpecaConfig(order=1, interval=4), sol, np.zeros(20, np.float32), lat, lab)
+    assert np.array_equal(out, plain)                     # bit-identical
+    assert np.all(tr.kind == KIND_FULL)
+
+
+def test_tiny_dit_default_thresholds_exercise_both_paths(tiny):
+    s, m, sol, lat, lab = tiny
+    tau = core.tau_linear(0.05, 0.01, 20)
+    out, tr = sampler.sample(m, sampler.SpecaConfig(order=1, interval=4), sol, tau, lat, lab)
+    assert (tr.kind == KIND_SPEC).sum() > 5 and (tr.kind == KIND_REJECT).sum() > 5
+    assert not np.array_equal(tr.kind[0], tr.kind[1])     # sample-adaptive: schedules differ
+    # never more than N-1 speculative steps in a row
+    for b in range(2):
+        run = 0
+        for k in tr.kind[b]:
+            run = run + 1 if k == KIND_SPEC else 0
+            assert run <= 3
+    # speculation changes the result a little, not wildly
+    plain = sampler.sample_plain(m, sol, lat, lab)
+    rel = np.abs(out - plain).max() / np.abs(plain).max()
+    assert 0 < rel < 0.2
+
+
+def test_tiny_dit_guided_runs(tiny):
+    s, m, _, lat, lab = tiny
+    ts, ab = si.ddim_tables(6)
+    sol = sampler.Solver("ddim", ts, ab, cfg_scale=1.5)
+    out, tr = sampler.sample(m, sampler.SpecaConfig(order=2, interval=3), sol, np.full(6, 1e9, np.float32), lat, lab)
+    assert tr.err.shape == (2, 6, 2) and tr.kind[0].tolist() == [0, 1, 1, 0, 1, 1]
+    assert np.all(np.isfinite(out))
