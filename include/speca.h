@@ -1,0 +1,236 @@
+/*
+ * speca.h - C ABI of the MI355X (gfx950) SpeCa sampling-step library.
+ *
+ * SpeCa ("forecast-then-verify" sampling for diffusion transformers):
+ *   (1) at a reference step the model runs in full and a per-slot cache of branch
+ *       features and their finite differences is refreshed (Sec. 3.2 step 1; Sec. 3.3, Eq. 3);
+ *   (2) at speculative steps every cached feature is forecast by a Taylor-series
+ *       combination of those differences (Sec. 3.3, Eq. 2);
+ *   (3) the forecast is verified at one deep block: that block is recomputed for real,
+ *       the relative L2 error between forecast and recomputed feature is compared with
+ *       a step-dependent threshold, the sample is accepted or falls back to full
+ *       compute (Sec. 3.4, Eq. 4, sequential validation, adaptive threshold).
+ *
+ * Conventions
+ *   - "step" s = 0..S-1 counts sampling steps upwards (the paper's timestep t decreases).
+ *   - A "row" is one sequence of the model's batch.  With classifier-free guidance a
+ *     sample owns two rows (conditional b, unconditional B+b).
+ *   - A "slot" is one cached branch output [rows, tokens, hidden]: DiT blocks own two
+ *     (attention branch, MLP branch) in block order.
+ *   - DEVICE pointers are raw HIP device addresses owned by the caller (e.g. torch
+ *     tensors) unless stated otherwise; HOST pointers are ordinary process memory.
+ *   - Every function returns a speca_status; it never throws or aborts.  The message of
+ *     the last failure on a context is available from speca_last_error().
+ *   - All device work of a context is enqueued on the HIP stream given at creation.
+ *     Calls that return host results (speca_verify, speca_spec_step, speca_sample)
+ *     synchronise that stream before returning; the others are asynchronous.
+ *   - A context is not thread-safe; contexts are independent of each other.
+ */
+#ifndef SPECA_H
+#define SPECA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct speca_ctx speca_ctx;
+
+typedef enum speca_status {
+  SPECA_OK = 0,
+  SPECA_EINVAL = 1,        /* bad argument (null pointer, size, enum, row index) */
+  SPECA_ENOMEM = 2,        /* device or host allocation failed */
+  SPECA_ESTATE = 3,        /* call order: cache not initialised, row without a reference, ... */
+  SPECA_EHIP = 4,          /* a HIP runtime call or kernel launch failed */
+  SPECA_EUNSUPPORTED = 5   /* valid request this build does not implement */
+} speca_status;
+
+enum { SPECA_F32 = 0, SPECA_BF16 = 1 };                       /* storage types */
+enum { SPECA_MODEL_NONE = 0, SPECA_MODEL_DIT = 1, SPECA_MODEL_MMDIT = 2 };
+enum { SPECA_COEF_TAYLOR = 0, SPECA_COEF_NEWTON = 1 };
+enum { SPECA_SOLVER_DDIM = 0, SPECA_SOLVER_FLOW = 1 };
+enum { SPECA_KIND_FULL = 0, SPECA_KIND_SPEC = 1, SPECA_KIND_REJECT = 2 };
+enum { SPECA_METRIC_L2 = 0, SPECA_METRIC_L1 = 1, SPECA_METRIC_LINF = 2, SPECA_METRIC_COSINE = 3 };
+
+#define SPECA_MAX_ORDER 4          /* highest Taylor order m the cache can hold */
+#define SPECA_MAX_LAUNCH_ROWS 64   /* rows handled by one internal launch; larger lists are chunked */
+
+/* Shape of the target model (Sec. 3.1.2 names the architecture; sizes are the caller's).
+ * kind NONE describes a bare cache (n_slots x tokens x hidden) with no model attached:
+ * only init_cache / refresh / forecast / verify are available on such a context. */
+typedef struct speca_model_desc {
+  int32_t kind;            /* SPECA_MODEL_* */
+  int32_t dtype;           /* SPECA_F32 | SPECA_BF16: weights, activations, cache */
+  int32_t depth;           /* DiT: blocks.  MMDiT: dual-stream blocks */
+  int32_t depth_single;    /* MMDiT: single-stream blocks (0 for DiT) */
+  int32_t hidden;          /* D */
+  int32_t heads;           /* H; head_dim = D / H */
+  int32_t mlp_hidden;      /* Dm */
+  int32_t in_channels;     /* latent channels C */
+  int32_t latent_t;        /* latent frames (1 for images) */
+  int32_t latent_h;
+  int32_t latent_w;
+  int32_t patch;           /* spatial patch p (tokens = t * h/p * w/p) */
+  int32_t num_classes;     /* DiT: label table has num_classes+1 rows, the last is the null label */
+  int32_t freq_dim;        /* width of the sinusoidal timestep embedding */
+  int32_t txt_tokens;      /* MMDiT */
+  int32_t txt_dim;         /* MMDiT */
+  int32_t vec_dim;         /* MMDiT pooled-conditioning width */
+  int32_t n_slots;         /* kind NONE only */
+  int32_t tokens;          /* kind NONE only */
+} speca_model_desc;
+
+/* Table of caller-owned DEVICE tensors, looked up by name ("blk3.qkv_w", ...).
+ * Linear weights are [out_features, in_features] row-major in the model dtype.
+ * numel[i] is checked against the shape the descriptor implies. */
+typedef struct speca_weights {
+  int32_t count;
+  const char* const* names;     /* HOST */
+  const void* const* ptrs;      /* HOST array of DEVICE pointers */
+  const int64_t* numel;         /* HOST */
+} speca_weights;
+
+/* SpeCa hyper-parameters (Sec. 3.3: order m, interval N; Sec. 3.4: eps; appendix:
+ * forced activation period, verify layer). */
+typedef struct speca_cfg {
+  int32_t order;           /* m, 0..SPECA_MAX_ORDER */
+  int32_t interval;        /* N >= 1: a full step is forced once step - last_full >= N */
+  int32_t verify_block;    /* block recomputed for verification; -1 = last block */
+  int32_t coef_mode;       /* SPECA_COEF_TAYLOR (Eq. 2 as printed) | SPECA_COEF_NEWTON */
+  float   eps;             /* Eq. 4 epsilon, paper value 1e-8 */
+  int32_t warmup_full;     /* steps 0..warmup_full-1 are always full (>= 1) */
+  int32_t metric;          /* SPECA_METRIC_*; L2 is Eq. 4 */
+} speca_cfg;
+
+/* Conditioning of one call. */
+typedef struct speca_cond {
+  const int32_t* labels;   /* HOST.  DiT: one class label per row (per sample for speca_sample) */
+  const void* txt;         /* DEVICE. MMDiT text tokens [rows, txt_tokens, txt_dim], model dtype */
+  const void* pooled;      /* DEVICE. MMDiT pooled vector [rows, vec_dim], model dtype */
+  float timestep;          /* value the model is conditioned on (ignored by speca_sample) */
+} speca_cond;
+
+/* Solver tables are data (the method is independent of the noise schedule). */
+typedef struct speca_solver {
+  int32_t kind;            /* SPECA_SOLVER_DDIM (eta = 0) | SPECA_SOLVER_FLOW (Euler) */
+  int32_t steps;           /* S */
+  const float* timesteps;  /* HOST [S]   conditioning value of step s */
+  const float* table;      /* HOST [S+1] alpha_bar (DDIM; last entry 1) or sigma (flow; last entry 0) */
+  float cfg_scale;         /* > 0: classifier-free guidance, rows = 2 x batch, null label for the second half */
+} speca_solver;
+
+/* Per-sample, per-step record of speca_sample.  All HOST memory owned by the caller;
+ * any pointer may be NULL. */
+typedef struct speca_trace {
+  int8_t* kind;            /* [batch][S]      SPECA_KIND_* */
+  float*  err;             /* [batch][S][2]   Eq. 4 error per row of the sample (NaN = not verified / no second row) */
+  int32_t n_full;          /* out: sample-steps computed in full (scheduled or after a rejection) */
+  int32_t n_spec;          /* out: sample-steps accepted */
+  int32_t n_reject;        /* out: speculative attempts rejected */
+} speca_trace;
+
+/* ---- life cycle ------------------------------------------------------------------- */
+
+/* Create a context for `desc` with weights `w` (may be NULL for kind NONE) on HIP stream
+ * `hip_stream` (a hipStream_t; NULL = the null stream).  The weight tensors must outlive
+ * the context.  Allocates no cache yet. */
+int speca_create(speca_ctx** out, const speca_model_desc* desc, const speca_weights* w, void* hip_stream);
+int speca_destroy(speca_ctx* ctx);
+/* Message of the last failed call on ctx (ctx == NULL: of the last failed create). */
+const char* speca_last_error(const speca_ctx* ctx);
+
+/* ---- (1) cache --------------------------------------------------------------------- */
+
+/* Allocate (or re-use) and reset the cache [slot][order 0..m][batch_rows][tokens][hidden]
+ * and the per-row reference history; also sizes the activation workspace for batch_rows.
+ * May be called again to start a new trajectory.  Sec. 3.3 (features + differences). */
+int speca_init_cache(speca_ctx* ctx, const speca_cfg* cfg, int batch_rows);
+
+/* Cache refresh from materialised features (the cache-only form of a reference step):
+ * features is DEVICE [n_slots][n_rows][tokens][hidden] in the cache dtype, row i of it
+ * belongs to cache row rows[i] (HOST, strictly increasing).  For every listed row stores
+ * D0 <- F and D^i <- (D^{i-1}_new - D^{i-1}_old) / d_i, i <= min(m, #references so far),
+ * then records `step` as the row's latest reference.  d_i = step - last reference
+ * (TAYLOR; with a uniform gap N this is Eq. 3 scaled by N^-i) or step - i-th last
+ * reference (NEWTON).  step must exceed the row's latest reference.  Asynchronous. */
+int speca_refresh(speca_ctx* ctx, int step, const int32_t* rows, int n_rows, const void* features);
+
+/* ---- (2) reference step ---------------------------------------------------------------- */
+
+/* Full forward of the model for the listed rows at sampling step `step`, with cache
+ * refresh fused into the branch epilogues.  x: DEVICE fp32 [batch_rows, C, (T,) H, W]
+ * (all rows present; only the listed ones are read).  model_out: DEVICE fp32, same shape;
+ * only the listed rows are written.  Sec. 3.2 step 1.  Asynchronous. */
+int speca_full_step(speca_ctx* ctx, const void* x, const speca_cond* cond, int step,
+                    const int32_t* rows, int n_rows, void* model_out);
+
+/* ---- (3) forecast ---------------------------------------------------------------------- */
+
+/* Eq. 2 for every slot of the listed rows at distance k = step - latest reference of the
+ * row (each row may have its own k and its own available order).  out_features: DEVICE
+ * [n_slots][n_rows][tokens][hidden] in the cache dtype.  A row without a reference, or
+ * with step <= its latest reference, is SPECA_ESTATE.  Asynchronous. */
+int speca_forecast(speca_ctx* ctx, int step, const int32_t* rows, int n_rows, void* out_features);
+
+/* ---- (4) verification ------------------------------------------------------------------ */
+
+/* Eq. 4 on two DEVICE tensors [n_rows][elems_per_row] of type dtype:
+ * err[r] = ||pred_r - truth_r||_2 / (||truth_r||_2 + eps) (or the cfg metric), fp32, fixed
+ * summation order (bit-reproducible, independent of n_rows); accept[r] = err[r] <= tau[r].
+ * tau_per_row, err_out, accept_out are HOST arrays of n_rows; tau_per_row may be NULL
+ * (then accept_out is not written).  Synchronises. */
+int speca_verify(speca_ctx* ctx, const void* pred, const void* truth, int n_rows, int64_t elems_per_row,
+                 int dtype, const float* tau_per_row, float eps, float* err_out, uint8_t* accept_out);
+
+/* Speculative attempt (Sec. 3.2 steps 2-3) for the listed rows at `step`: forecast all
+ * slots and fold them, gated by the step's own modulation, into the hidden state up to
+ * the verify block; run the verify block for real; Eq. 4 between the forecast and the
+ * recomputed last slot of that block; rows whose error passes tau_per_row are finished
+ * with forecasts for all remaining blocks and their model_out rows are written.  With
+ * pair_stride > 0 rows r and r + pair_stride (both must be listed) are accepted only
+ * together.  err_out / accept_out: HOST [n_rows].  The cache is not modified.  Synchronises. */
+int speca_spec_step(speca_ctx* ctx, const void* x, const speca_cond* cond, int step,
+                    const int32_t* rows, int n_rows, const float* tau_per_row, int pair_stride,
+                    float* err_out, uint8_t* accept_out, void* model_out);
+
+/* ---- (5) whole trajectory -------------------------------------------------------------- */
+
+/* SpeCa sampling of `batch` samples (batch_rows of the cache must be batch, or 2*batch
+ * with guidance): per step each sample is scheduled full or speculative, speculative
+ * samples are verified against tau[step], rejected ones are recomputed in full at the
+ * same step, then the solver update is applied.  tau[s] <= 0 makes step s full.
+ * latents_inout: DEVICE fp32 [batch, C, (T,) H, W], overwritten with the final latents.
+ * tau: HOST [S].  Re-initialises the cache state.  Synchronises. */
+int speca_sample(speca_ctx* ctx, void* latents_inout, int batch, const speca_cond* cond,
+                 const speca_solver* solver, const float* tau, speca_trace* trace_out);
+
+/* ---- host-only helpers (no device work; usable without a GPU) ----------------------------- */
+
+/* tau[s] = tau0 * beta^(s/S)   (Sec. 3.4.2 adaptive threshold, progress (T-t)/T = s/S). */
+int speca_tau_geometric(float tau0, float beta, int steps, float* tau_out);
+/* tau[s] = tau_start + (tau_end - tau_start) * s/(S-1). */
+int speca_tau_linear(float tau_start, float tau_end, int steps, float* tau_out);
+/* Forecast weights c[0..order] for `step` given the references (latest first). */
+int speca_coefficients(int coef_mode, int step, const int32_t* refs, int n_refs, int order, float* c_out);
+/* Refresh divisors d[1..order] written to d_out[0..order-1]. */
+int speca_divisors(int coef_mode, int step, const int32_t* refs, int n_refs, int order, float* d_out);
+
+/* The per-sample schedule state machine of speca_sample, exposed for host-side testing.
+ * plan: fills spec_out / full_out (HOST, capacity batch) with the samples to attempt
+ * speculatively / to compute in full at `step` under threshold tau_s.
+ * commit: accept[i] (HOST) is the verdict for spec list entry i of the last plan; rejected
+ * samples and the planned-full ones take `step` as new reference.  kind_out (HOST [batch],
+ * may be NULL) receives SPECA_KIND_* of every sample for this step. */
+typedef struct speca_sched speca_sched;
+int speca_sched_create(speca_sched** out, int batch, const speca_cfg* cfg);
+int speca_sched_destroy(speca_sched* s);
+int speca_sched_plan(speca_sched* s, int step, float tau_s, int32_t* spec_out, int* n_spec, int32_t* full_out, int* n_full);
+int speca_sched_commit(speca_sched* s, int step, const uint8_t* accept, int8_t* kind_out);
+/* References of one sample, latest first; returns their count via n_out (<= order+1). */
+int speca_sched_refs(const speca_sched* s, int sample, int32_t* refs_out, int* n_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECA_H */

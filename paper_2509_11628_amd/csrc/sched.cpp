@@ -1,0 +1,155 @@
+// Host-side schedule logic (see sched.h).  No device code.
+#include "sched.h"
+
+#include <cmath>
+#include <cstring>
+#include <new>
+
+namespace speca {
+
+bool forecast_coefficients(int mode, int step, const int32_t* refs, int n_refs, int order, float* c) {
+  if (!refs || !c || n_refs < 1 || order < 0 || order > SPECA_MAX_ORDER || order > n_refs - 1) return false;
+  const int k = step - refs[0];
+  if (k <= 0) return false;
+  if (mode == SPECA_COEF_TAYLOR) {
+    double p = 1.0, fact = 1.0;
+    for (int i = 0; i <= order; ++i) {
+      if (i > 0) { p *= static_cast<double>(k); fact *= static_cast<double>(i); }
+      c[i] = static_cast<float>(p / fact);
+    }
+    return true;
+  }
+  if (mode == SPECA_COEF_NEWTON) {
+    double p = 1.0;
+    for (int i = 0; i <= order; ++i) {
+      c[i] = static_cast<float>(p);
+      p *= static_cast<double>(step - refs[i]);
+    }
+    return true;
+  }
+  return false;
+}
+
+bool refresh_divisors(int mode, int step, const int32_t* refs, int n_refs, int order, float* d) {
+  if (order == 0) return true;
+  if (!refs || !d || order < 0 || order > SPECA_MAX_ORDER || n_refs < order) return false;
+  for (int i = 1; i <= order; ++i) {
+    int div;
+    if (mode == SPECA_COEF_TAYLOR) div = step - refs[0];
+    else if (mode == SPECA_COEF_NEWTON) div = step - refs[i - 1];
+    else return false;
+    if (div <= 0) return false;
+    d[i - 1] = static_cast<float>(div);
+  }
+  return true;
+}
+
+void tau_geometric(float tau0, float beta, int steps, float* out) {
+  for (int s = 0; s < steps; ++s)
+    out[s] = static_cast<float>(static_cast<double>(tau0) * std::pow(static_cast<double>(beta), static_cast<double>(s) / steps));
+}
+
+void tau_linear(float a, float b, int steps, float* out) {
+  if (steps == 1) { out[0] = a; return; }
+  for (int s = 0; s < steps; ++s)
+    out[s] = static_cast<float>(static_cast<double>(a) + (static_cast<double>(b) - static_cast<double>(a)) * (static_cast<double>(s) / (steps - 1)));
+}
+
+}  // namespace speca
+
+static bool cfg_valid(const speca_cfg* c) {
+  return c && c->order >= 0 && c->order <= SPECA_MAX_ORDER && c->interval >= 1 && c->warmup_full >= 1 &&
+         (c->coef_mode == SPECA_COEF_TAYLOR || c->coef_mode == SPECA_COEF_NEWTON) && c->eps >= 0.0f &&
+         c->metric >= SPECA_METRIC_L2 && c->metric <= SPECA_METRIC_COSINE && c->verify_block >= -1;
+}
+
+extern "C" {
+
+int speca_tau_geometric(float tau0, float beta, int steps, float* tau_out) {
+  if (!tau_out || steps < 1 || !(beta > 0.0f)) return SPECA_EINVAL;
+  speca::tau_geometric(tau0, beta, steps, tau_out);
+  return SPECA_OK;
+}
+
+int speca_tau_linear(float tau_start, float tau_end, int steps, float* tau_out) {
+  if (!tau_out || steps < 1) return SPECA_EINVAL;
+  speca::tau_linear(tau_start, tau_end, steps, tau_out);
+  return SPECA_OK;
+}
+
+int speca_coefficients(int coef_mode, int step, const int32_t* refs, int n_refs, int order, float* c_out) {
+  return speca::forecast_coefficients(coef_mode, step, refs, n_refs, order, c_out) ? SPECA_OK : SPECA_EINVAL;
+}
+
+int speca_divisors(int coef_mode, int step, const int32_t* refs, int n_refs, int order, float* d_out) {
+  if (order < 0 || (order > 0 && !d_out)) return SPECA_EINVAL;
+  return speca::refresh_divisors(coef_mode, step, refs, n_refs, order, d_out) ? SPECA_OK : SPECA_EINVAL;
+}
+
+int speca_sched_create(speca_sched** out, int batch, const speca_cfg* cfg) {
+  if (!out) return SPECA_EINVAL;
+  *out = nullptr;
+  if (batch < 1 || !cfg_valid(cfg)) return SPECA_EINVAL;
+  speca_sched* s = new (std::nothrow) speca_sched();
+  if (!s) return SPECA_ENOMEM;
+  s->batch = batch;
+  s->cfg = *cfg;
+  s->refs.assign(batch, speca::RefHistory());
+  *out = s;
+  return SPECA_OK;
+}
+
+int speca_sched_destroy(speca_sched* s) {
+  delete s;
+  return SPECA_OK;
+}
+
+// A sample speculates at `step` iff it has a reference, fewer than N steps have passed since
+// it, the warm-up is over and the threshold is positive; otherwise it is computed in full.
+int speca_sched_plan(speca_sched* s, int step, float tau_s, int32_t* spec_out, int* n_spec, int32_t* full_out, int* n_full) {
+  if (!s || !spec_out || !n_spec || !full_out || !n_full || step < 0) return SPECA_EINVAL;
+  s->planned_spec.clear();
+  s->planned_full.clear();
+  for (int b = 0; b < s->batch; ++b) {
+    const speca::RefHistory& h = s->refs[b];
+    if (h.n > 0 && step <= h.r[0]) return SPECA_ESTATE;
+    const bool spec = h.n >= 1 && (step - h.r[0]) < s->cfg.interval && step >= s->cfg.warmup_full && tau_s > 0.0f;
+    (spec ? s->planned_spec : s->planned_full).push_back(b);
+  }
+  *n_spec = static_cast<int>(s->planned_spec.size());
+  *n_full = static_cast<int>(s->planned_full.size());
+  for (int i = 0; i < *n_spec; ++i) spec_out[i] = s->planned_spec[i];
+  for (int i = 0; i < *n_full; ++i) full_out[i] = s->planned_full[i];
+  s->planned_step = step;
+  return SPECA_OK;
+}
+
+int speca_sched_commit(speca_sched* s, int step, const uint8_t* accept, int8_t* kind_out) {
+  if (!s || step != s->planned_step) return s ? SPECA_ESTATE : SPECA_EINVAL;
+  if (!s->planned_spec.empty() && !accept) return SPECA_EINVAL;
+  for (size_t i = 0; i < s->planned_spec.size(); ++i) {
+    const int b = s->planned_spec[i];
+    if (accept[i]) {
+      if (kind_out) kind_out[b] = SPECA_KIND_SPEC;          // accepted: cache and references untouched
+    } else {
+      s->refs[b].push(step, s->cfg.order);                  // rejected: recomputed in full, new reference
+      if (kind_out) kind_out[b] = SPECA_KIND_REJECT;
+    }
+  }
+  for (int b : s->planned_full) {
+    s->refs[b].push(step, s->cfg.order);
+    if (kind_out) kind_out[b] = SPECA_KIND_FULL;
+  }
+  s->planned_step = -1;
+  return SPECA_OK;
+}
+
+int speca_sched_refs(const speca_sched* s, int sample, int32_t* refs_out, int* n_out) {
+  if (!s || !refs_out || !n_out || sample < 0 || sample >= s->batch) return SPECA_EINVAL;
+  const speca::RefHistory& h = s->refs[sample];
+  *n_out = h.n;
+  for (int i = 0; i < h.n; ++i) refs_out[i] = h.r[i];
+  return SPECA_OK;
+}
+
+}  // extern "C"
