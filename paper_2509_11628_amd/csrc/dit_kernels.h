@@ -1,0 +1,26 @@
+// Launchers of the small DiT kernels (see dit_kernels.hip).
+#pragma once
+
+#include "common.h"
+
+namespace speca {
+
+// Per-launch integer table passed by value: labels, source rows or destination rows of
+// the compact rows of a launch.
+struct RowLabels {
+  int32_t v[kMaxRows];
+};
+
+Error launch_sinusoid(int dtype, void* emb, int n, int dim, float t, hipStream_t st);
+Error launch_cond_sum(int dtype, const float* temb, const void* y_table, const RowLabels& labels, int n, int D, void* sc, hipStream_t st);
+Error launch_patch_embed(int dtype, const float* x, const RowLabels& xrow, const void* Wp, const void* bp, const void* pos, float* h,
+                         int n, int C, int Hh, int Ww, int p, int D, hipStream_t st);
+// y = LN(h) * (1 + scale[row]) + shift[row]; shift/scale rows are mod_stride floats apart.
+Error launch_ln_modulate(int dtype, const float* h, const float* shift, const float* scale, int64_t mod_stride, void* y,
+                         int64_t n_tokens, int tokens_per_row, int D, hipStream_t st);
+// h_out = h_in + sum over slots [s0, s1) of gate * forecast (Eq. 2 fused into the residual stream).
+Error launch_forecast_fold(const CacheGeom& g, const RowTable& rt, const float* h_in, float* h_out, const float* mod,
+                           int64_t mod_stride, const int32_t* gate_off_dev, int s0, int s1, int D, hipStream_t st);
+Error launch_unpatchify(const float* tok, const RowLabels& rows, float* out, int n, int C, int Hh, int Ww, int p, hipStream_t st);
+
+}  // namespace speca

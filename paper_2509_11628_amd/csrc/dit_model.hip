@@ -1,6 +1,313 @@
+// Class-conditional DiT in adaLN-Zero form (Sec. 3.1.2: blocks of attention and MLP in the
+// residual form x + AdaLN o f(x)) as the target model of the SpeCa step: the reference
+// (full) step with the cache refresh fused into the branch epilogues, and the speculative
+// attempt (forecast-and-fold, real verify block, Eq. 4, unconditional finish).
+//
+//   c      = MLP_t(sinusoid(t)) + y_table[label]
+//   h0     = patchify(x) Wp^T + bp + pos
+//   block: (shift_a, scale_a, gate_a, shift_m, scale_m, gate_m) = SiLU(c) Wmod^T + bmod
+//          F_attn = proj(MHA(LN(h)(1+scale_a)+shift_a))        -> cache slot 2l,   h += gate_a F_attn
+//          F_mlp  = fc2(GELU(fc1(LN(h)(1+scale_m)+shift_m)))   -> cache slot 2l+1, h += gate_m F_mlp
+//   out    = unpatchify((LN(h)(1+scale_f)+shift_f) Wf^T + bf)
+#include <cstring>
+#include <map>
+#include <string>
+
+#include "dit_kernels.h"
+#include "gemm.h"
+#include "kernels.h"
 #include "model.h"
+
 namespace speca {
-Error make_dit_model(const speca_model_desc&, const speca_weights*, std::unique_ptr<Model>*) {
-  SPECA_FAIL(SPECA_EUNSUPPORTED, "DiT model not built yet");
+
+namespace {
+
+struct BlockW {
+  const void *qkv_w, *qkv_b, *proj_w, *proj_b, *fc1_w, *fc1_b, *fc2_w, *fc2_b;
+};
+
+struct DiT final : Model {
+  speca_model_desc d{};
+  int D = 0, Dm = 0, H = 0, hd = 0, L = 0, T = 0, Kp = 0;
+  size_t esz = 4;
+  // weights (caller-owned)
+  const void *t_w1 = nullptr, *t_b1 = nullptr, *t_w2 = nullptr, *t_b2 = nullptr, *y_table = nullptr;
+  const void *patch_w = nullptr, *patch_b = nullptr, *pos = nullptr, *final_w = nullptr, *final_b = nullptr;
+  std::vector<BlockW> blk;
+  // library-owned: all modulation weights [L*6D + 2D, D] and biases concatenated, so that the
+  // modulation of every block (and the final layer) is one GEMM per step
+  void* mod_w = nullptr;
+  void* mod_b = nullptr;
+  int64_t mod_n = 0;                 // L*6D + 2D
+  int32_t* gate_off_dev = nullptr;   // [2L] offset of each slot's gate inside a modulation row
+  // workspace for up to cap_rows rows
+  int cap_rows = 0;
+  void *emb = nullptr, *t_hid = nullptr, *sc = nullptr, *xn = nullptr, *qkv = nullptr, *att = nullptr, *f1 = nullptr;
+  float *temb = nullptr, *mod = nullptr, *h = nullptr, *h2 = nullptr, *feat = nullptr, *tok = nullptr;
+
+  ~DiT() override {
+    for (void* p : {mod_w, mod_b, static_cast<void*>(gate_off_dev)})
+      if (p) (void)hipFree(p);
+    free_ws();
+  }
+  void free_ws() {
+    for (void* p : {emb, t_hid, sc, xn, qkv, att, f1, static_cast<void*>(temb), static_cast<void*>(mod), static_cast<void*>(h),
+                    static_cast<void*>(h2), static_cast<void*>(feat), static_cast<void*>(tok)})
+      if (p) (void)hipFree(p);
+    emb = t_hid = sc = xn = qkv = att = f1 = nullptr;
+    temb = mod = h = h2 = feat = tok = nullptr;
+    cap_rows = 0;
+  }
+
+  int n_slots() const override { return 2 * L; }
+  int n_blocks() const override { return L; }
+  int64_t tokens() const override { return T; }
+  int hidden() const override { return D; }
+  int64_t latent_elems() const override { return static_cast<int64_t>(d.in_channels) * d.latent_h * d.latent_w; }
+
+  Error prepare(speca_ctx* ctx, int batch_rows) override {
+    const int rows = std::min(batch_rows, kMaxRows);
+    if (rows <= cap_rows) return ok();
+    SPECA_HIP(hipStreamSynchronize(ctx->stream));
+    free_ws();
+    const size_t R = rows, TT = static_cast<size_t>(T);
+    auto alloc = [](void** p, size_t bytes) { return hipMalloc(p, bytes) == hipSuccess; };
+    bool good = alloc(&emb, R * d.freq_dim * esz) && alloc(&t_hid, R * D * esz) && alloc(&sc, R * D * esz) &&
+                alloc(&xn, R * TT * D * esz) && alloc(&qkv, R * TT * 3 * D * esz) && alloc(&att, R * TT * D * esz) &&
+                alloc(&f1, R * TT * Dm * esz) && alloc(reinterpret_cast<void**>(&temb), R * D * 4) &&
+                alloc(reinterpret_cast<void**>(&mod), R * mod_n * 4) && alloc(reinterpret_cast<void**>(&h), R * TT * D * 4) &&
+                alloc(reinterpret_cast<void**>(&h2), R * TT * D * 4) && alloc(reinterpret_cast<void**>(&feat), R * TT * D * 4) &&
+                alloc(reinterpret_cast<void**>(&tok), R * TT * Kp * 4);
+    if (!good) {
+      (void)hipGetLastError();
+      free_ws();
+      SPECA_FAIL(SPECA_ENOMEM, "cannot allocate the activation workspace for %d rows", rows);
+    }
+    cap_rows = rows;
+    return ok();
+  }
+
+  // conditioning + modulation of all blocks for compact rows 0..n-1 (labels of rows[i])
+  Error conditioning(hipStream_t st, float t, const int32_t* labels_per_row, const int32_t* rows, int n) {
+    RowLabels lab{};
+    for (int i = 0; i < n; ++i) lab.v[i] = labels_per_row[rows[i]];
+    SPECA_TRY(launch_sinusoid(d.dtype, emb, n, d.freq_dim, t, st));
+    GemmEpi e1;
+    e1.mode = EPI_SILU; e1.bias = t_b1; e1.out = t_hid; e1.ldo = D;
+    SPECA_TRY(launch_gemm(d.dtype, emb, d.freq_dim, t_w1, d.freq_dim, n, D, d.freq_dim, e1, st));
+    GemmEpi e2;
+    e2.mode = EPI_F32; e2.bias = t_b2; e2.out = temb; e2.ldo = D;
+    SPECA_TRY(launch_gemm(d.dtype, t_hid, D, t_w2, D, n, D, D, e2, st));
+    SPECA_TRY(launch_cond_sum(d.dtype, temb, y_table, lab, n, D, sc, st));
+    GemmEpi e3;
+    e3.mode = EPI_F32; e3.bias = mod_b; e3.out = mod; e3.ldo = mod_n;
+    SPECA_TRY(launch_gemm(d.dtype, sc, D, mod_w, D, n, static_cast<int>(mod_n), D, e3, st));
+    return ok();
+  }
+
+  Error embed(hipStream_t st, const float* x, int x_mod, const int32_t* rows, int n) {
+    RowLabels xr{};
+    for (int i = 0; i < n; ++i) xr.v[i] = rows[i] % x_mod;
+    return launch_patch_embed(d.dtype, x, xr, patch_w, patch_b, pos, h, n, d.in_channels, d.latent_h, d.latent_w, d.patch, D, st);
+  }
+
+  const float* mod_at(int l, int which) const { return mod + static_cast<int64_t>(l) * 6 * D + static_cast<int64_t>(which) * D; }
+
+  // attention branch of block l on hidden state hs: hs += gate_a * proj(MHA(LNmod(hs)))
+  Error attn_branch(speca_ctx* ctx, int l, float* hs, int n, const RowTable* refresh_rt) {
+    hipStream_t st = ctx->stream;
+    const int64_t M = static_cast<int64_t>(n) * T;
+    SPECA_TRY(launch_ln_modulate(d.dtype, hs, mod_at(l, 0), mod_at(l, 1), mod_n, xn, M, T, D, st));
+    GemmEpi e;
+    e.mode = EPI_STORE; e.bias = blk[l].qkv_b; e.out = qkv; e.ldo = 3 * D;
+    SPECA_TRY(launch_gemm(d.dtype, xn, D, blk[l].qkv_w, D, static_cast<int>(M), 3 * D, D, e, st));
+    SPECA_TRY(launch_attention(d.dtype, qkv, att, n, T, H, hd, st));
+    GemmEpi b;
+    b.mode = EPI_BRANCH; b.bias = blk[l].proj_b; b.h = hs; b.ldh = D; b.gate = mod_at(l, 2); b.gate_stride = mod_n; b.tokens = T;
+    if (refresh_rt) { b.refresh = 1; b.slot = 2 * l; b.g = ctx->geom; b.rt = *refresh_rt; }
+    SPECA_TRY(launch_gemm(d.dtype, att, D, blk[l].proj_w, D, static_cast<int>(M), D, D, b, st));
+    return ok();
+  }
+
+  // MLP branch of block l.  truth_out != nullptr: only materialise F_mlp (fp32) there, no residual, no refresh.
+  Error mlp_branch(speca_ctx* ctx, int l, float* hs, int n, const RowTable* refresh_rt, float* truth_out) {
+    hipStream_t st = ctx->stream;
+    const int64_t M = static_cast<int64_t>(n) * T;
+    SPECA_TRY(launch_ln_modulate(d.dtype, hs, mod_at(l, 3), mod_at(l, 4), mod_n, xn, M, T, D, st));
+    GemmEpi e;
+    e.mode = EPI_GELU; e.bias = blk[l].fc1_b; e.out = f1; e.ldo = Dm;
+    SPECA_TRY(launch_gemm(d.dtype, xn, D, blk[l].fc1_w, D, static_cast<int>(M), Dm, D, e, st));
+    GemmEpi b;
+    b.bias = blk[l].fc2_b;
+    if (truth_out) {
+      b.mode = EPI_F32; b.out = truth_out; b.ldo = D;
+    } else {
+      b.mode = EPI_BRANCH; b.h = hs; b.ldh = D; b.gate = mod_at(l, 5); b.gate_stride = mod_n; b.tokens = T;
+      if (refresh_rt) { b.refresh = 1; b.slot = 2 * l + 1; b.g = ctx->geom; b.rt = *refresh_rt; }
+    }
+    SPECA_TRY(launch_gemm(d.dtype, f1, Dm, blk[l].fc2_w, Dm, static_cast<int>(M), D, Dm, b, st));
+    return ok();
+  }
+
+  Error final_layer(speca_ctx* ctx, const float* hs, const int32_t* rows, int n, float* model_out) {
+    hipStream_t st = ctx->stream;
+    const int64_t M = static_cast<int64_t>(n) * T;
+    const float* fm = mod + static_cast<int64_t>(L) * 6 * D;
+    SPECA_TRY(launch_ln_modulate(d.dtype, hs, fm, fm + D, mod_n, xn, M, T, D, st));
+    GemmEpi e;
+    e.mode = EPI_F32; e.bias = final_b; e.out = tok; e.ldo = Kp;
+    SPECA_TRY(launch_gemm(d.dtype, xn, D, final_w, D, static_cast<int>(M), Kp, D, e, st));
+    RowLabels r{};
+    for (int i = 0; i < n; ++i) r.v[i] = rows[i];
+    return launch_unpatchify(tok, r, model_out, n, d.in_channels, d.latent_h, d.latent_w, d.patch, st);
+  }
+
+  Error full_step(speca_ctx* ctx, const float* x, int x_mod, const speca_cond* cond, const int32_t* labels_per_row, int step,
+                  const int32_t* rows, int n, float* model_out) override {
+    if (n > cap_rows) SPECA_FAIL(SPECA_EUNSUPPORTED, "at most %d rows per launch", cap_rows);
+    RowTable rt;
+    SPECA_TRY(build_refresh_table(ctx, step, rows, n, &rt));
+    SPECA_TRY(conditioning(ctx->stream, cond->timestep, labels_per_row, rows, n));
+    SPECA_TRY(embed(ctx->stream, x, x_mod, rows, n));
+    for (int l = 0; l < L; ++l) {
+      SPECA_TRY(attn_branch(ctx, l, h, n, &rt));
+      SPECA_TRY(mlp_branch(ctx, l, h, n, &rt, nullptr));
+    }
+    SPECA_TRY(final_layer(ctx, h, rows, n, model_out));
+    push_refs(ctx, step, rows, n);
+    return ok();
+  }
+
+  Error spec_step(speca_ctx* ctx, const float* x, int x_mod, const speca_cond* cond, const int32_t* labels_per_row, int step,
+                  const int32_t* rows, int n, const float* tau_per_row, int pair_stride, float* model_out) override {
+    if (n > cap_rows) SPECA_FAIL(SPECA_EUNSUPPORTED, "at most %d rows per launch", cap_rows);
+    hipStream_t st = ctx->stream;
+    RowTable rt;
+    SPECA_TRY(build_forecast_table(ctx, step, rows, n, &rt));
+    // pairs: partner of rows[i] must be listed
+    std::vector<int> partner(n, -1);
+    if (pair_stride > 0) {
+      std::map<int, int> where;
+      for (int i = 0; i < n; ++i) where[rows[i]] = i;
+      for (int i = 0; i < n; ++i) {
+        const int other = rows[i] < pair_stride ? rows[i] + pair_stride : rows[i] - pair_stride;
+        auto it = where.find(other);
+        if (it == where.end()) SPECA_FAIL(SPECA_EINVAL, "row %d is listed without its pair row %d", rows[i], other);
+        partner[i] = it->second;
+      }
+    }
+    const int lv = ctx->cfg.verify_block >= 0 ? ctx->cfg.verify_block : L - 1;
+    SPECA_TRY(conditioning(st, cond->timestep, labels_per_row, rows, n));
+    SPECA_TRY(embed(st, x, x_mod, rows, n));
+    // Eq. 2 for every slot before the verify block, folded into h
+    SPECA_TRY(launch_forecast_fold(ctx->geom, rt, h, h, mod, mod_n, gate_off_dev, 0, 2 * lv, D, st));
+    // accepted path: forecasts for the verify block and everything after it -> h2
+    SPECA_TRY(launch_forecast_fold(ctx->geom, rt, h, h2, mod, mod_n, gate_off_dev, 2 * lv, 2 * L, D, st));
+    // the verify block for real, on h
+    SPECA_TRY(attn_branch(ctx, lv, h, n, nullptr));
+    SPECA_TRY(mlp_branch(ctx, lv, h, n, nullptr, feat));
+    // Eq. 4: forecast of slot 2lv+1 (formed on the fly from the cache) vs the recomputed feature
+    VerifyScratch& v = ctx->vs;
+    SPECA_TRY(ensure_partial(ctx, static_cast<size_t>(n) * verify_chunks(ctx->geom.E) * 3));
+    std::memcpy(v.h_tau, tau_per_row, n * sizeof(float));
+    SPECA_HIP(hipMemcpyAsync(v.tau_dev, v.h_tau, n * sizeof(float), hipMemcpyHostToDevice, st));
+    SPECA_TRY(launch_verify(ctx->cfg.metric, nullptr, ctx->geom.dtype, feat, SPECA_F32, ctx->geom.E, &ctx->geom, &rt, 2 * lv + 1, n,
+                            ctx->cfg.eps, v.tau_dev, v.partial, v.err_dev, v.acc_dev, st));
+    SPECA_HIP(hipMemcpyAsync(v.h_err, v.err_dev, n * sizeof(float), hipMemcpyDeviceToHost, st));
+    SPECA_HIP(hipMemcpyAsync(v.h_acc, v.acc_dev, n, hipMemcpyDeviceToHost, st));
+    // finish every listed row from h2 while the verdict travels; rejected rows are overwritten by the fallback
+    SPECA_TRY(final_layer(ctx, h2, rows, n, model_out));
+    SPECA_HIP(hipStreamSynchronize(st));
+    if (pair_stride > 0) {
+      std::vector<uint8_t> both(n);
+      for (int i = 0; i < n; ++i) both[i] = v.h_acc[i] && v.h_acc[partner[i]];
+      for (int i = 0; i < n; ++i) v.h_acc[i] = both[i];
+    }
+    return ok();
+  }
+};
+
+struct WeightLookup {
+  std::map<std::string, std::pair<const void*, int64_t>> tab;
+  Error get(const std::string& name, int64_t numel, const void** out) const {
+    auto it = tab.find(name);
+    if (it == tab.end()) SPECA_FAIL(SPECA_EINVAL, "weight '%s' is missing", name.c_str());
+    if (!it->second.first) SPECA_FAIL(SPECA_EINVAL, "weight '%s' is NULL", name.c_str());
+    if (it->second.second != numel)
+      SPECA_FAIL(SPECA_EINVAL, "weight '%s' has %lld elements, expected %lld", name.c_str(), static_cast<long long>(it->second.second),
+                 static_cast<long long>(numel));
+    *out = it->second.first;
+    return ok();
+  }
+};
+
+}  // namespace
+
+Error make_dit_model(const speca_model_desc& d, const speca_weights* w, std::unique_ptr<Model>* out) {
+  if (!w || w->count < 1 || !w->names || !w->ptrs || !w->numel) SPECA_FAIL(SPECA_EINVAL, "a DiT context needs a weight table");
+  if (d.depth < 1 || d.heads < 1 || d.hidden % d.heads) SPECA_FAIL(SPECA_EINVAL, "depth/heads/hidden = %d/%d/%d", d.depth, d.heads, d.hidden);
+  if (d.patch < 1 || d.latent_h % d.patch || d.latent_w % d.patch || d.latent_h < 1 || d.latent_w < 1)
+    SPECA_FAIL(SPECA_EINVAL, "latent %dx%d is not a multiple of patch %d", d.latent_h, d.latent_w, d.patch);
+  if (d.latent_t != 1) SPECA_FAIL(SPECA_EINVAL, "DiT takes image latents (latent_t = 1)");
+  if (d.in_channels < 1 || d.mlp_hidden < 1 || d.num_classes < 1 || d.freq_dim < 2 || d.freq_dim % 2)
+    SPECA_FAIL(SPECA_EINVAL, "in_channels/mlp_hidden/num_classes/freq_dim invalid");
+  std::unique_ptr<DiT> m(new DiT());
+  m->d = d;
+  m->D = d.hidden; m->Dm = d.mlp_hidden; m->H = d.heads; m->hd = d.hidden / d.heads; m->L = d.depth;
+  m->T = (d.latent_h / d.patch) * (d.latent_w / d.patch);
+  m->Kp = d.in_channels * d.patch * d.patch;
+  m->esz = dtype_size(d.dtype);
+  if (m->D % 8 || m->Dm % 8 || m->Kp % 4 || d.freq_dim % 8)
+    SPECA_FAIL(SPECA_EUNSUPPORTED, "hidden, mlp_hidden, freq_dim must be multiples of 8 and C*p*p of 4");
+  const int64_t D = m->D, Dm = m->Dm;
+  WeightLookup wl;
+  for (int i = 0; i < w->count; ++i) wl.tab[w->names[i] ? w->names[i] : ""] = {w->ptrs[i], w->numel[i]};
+  SPECA_TRY(wl.get("t_w1", D * d.freq_dim, &m->t_w1));
+  SPECA_TRY(wl.get("t_b1", D, &m->t_b1));
+  SPECA_TRY(wl.get("t_w2", D * D, &m->t_w2));
+  SPECA_TRY(wl.get("t_b2", D, &m->t_b2));
+  SPECA_TRY(wl.get("y_table", (d.num_classes + 1) * D, &m->y_table));
+  SPECA_TRY(wl.get("patch_w", D * m->Kp, &m->patch_w));
+  SPECA_TRY(wl.get("patch_b", D, &m->patch_b));
+  SPECA_TRY(wl.get("pos", static_cast<int64_t>(m->T) * D, &m->pos));
+  SPECA_TRY(wl.get("final_w", static_cast<int64_t>(m->Kp) * D, &m->final_w));
+  SPECA_TRY(wl.get("final_b", m->Kp, &m->final_b));
+  m->blk.resize(m->L);
+  m->mod_n = static_cast<int64_t>(m->L) * 6 * D + 2 * D;
+  SPECA_HIP(hipMalloc(&m->mod_w, static_cast<size_t>(m->mod_n) * D * m->esz));
+  SPECA_HIP(hipMalloc(&m->mod_b, static_cast<size_t>(m->mod_n) * m->esz));
+  for (int l = 0; l < m->L; ++l) {
+    const std::string p = "blk" + std::to_string(l) + ".";
+    BlockW& b = m->blk[l];
+    SPECA_TRY(wl.get(p + "qkv_w", 3 * D * D, &b.qkv_w));
+    SPECA_TRY(wl.get(p + "qkv_b", 3 * D, &b.qkv_b));
+    SPECA_TRY(wl.get(p + "proj_w", D * D, &b.proj_w));
+    SPECA_TRY(wl.get(p + "proj_b", D, &b.proj_b));
+    SPECA_TRY(wl.get(p + "fc1_w", Dm * D, &b.fc1_w));
+    SPECA_TRY(wl.get(p + "fc1_b", Dm, &b.fc1_b));
+    SPECA_TRY(wl.get(p + "fc2_w", D * Dm, &b.fc2_w));
+    SPECA_TRY(wl.get(p + "fc2_b", D, &b.fc2_b));
+    const void *mw, *mb;
+    SPECA_TRY(wl.get(p + "mod_w", 6 * D * D, &mw));
+    SPECA_TRY(wl.get(p + "mod_b", 6 * D, &mb));
+    SPECA_HIP(hipMemcpy(static_cast<char*>(m->mod_w) + static_cast<size_t>(l) * 6 * D * D * m->esz, mw, 6 * D * D * m->esz, hipMemcpyDeviceToDevice));
+    SPECA_HIP(hipMemcpy(static_cast<char*>(m->mod_b) + static_cast<size_t>(l) * 6 * D * m->esz, mb, 6 * D * m->esz, hipMemcpyDeviceToDevice));
+  }
+  const void *fw, *fb;
+  SPECA_TRY(wl.get("fmod_w", 2 * D * D, &fw));
+  SPECA_TRY(wl.get("fmod_b", 2 * D, &fb));
+  SPECA_HIP(hipMemcpy(static_cast<char*>(m->mod_w) + static_cast<size_t>(m->L) * 6 * D * D * m->esz, fw, 2 * D * D * m->esz, hipMemcpyDeviceToDevice));
+  SPECA_HIP(hipMemcpy(static_cast<char*>(m->mod_b) + static_cast<size_t>(m->L) * 6 * D * m->esz, fb, 2 * D * m->esz, hipMemcpyDeviceToDevice));
+  std::vector<int32_t> goff(2 * m->L);
+  for (int l = 0; l < m->L; ++l) {
+    goff[2 * l] = static_cast<int32_t>((static_cast<int64_t>(l) * 6 + 2) * D);
+    goff[2 * l + 1] = static_cast<int32_t>((static_cast<int64_t>(l) * 6 + 5) * D);
+  }
+  SPECA_HIP(hipMalloc(reinterpret_cast<void**>(&m->gate_off_dev), goff.size() * sizeof(int32_t)));
+  SPECA_HIP(hipMemcpy(m->gate_off_dev, goff.data(), goff.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+  SPECA_HIP(hipDeviceSynchronize());
+  out->reset(m.release());
+  return ok();
 }
-}
+
+}  // namespace speca

@@ -1,0 +1,246 @@
+"""Parity of the DiT reference step, the speculative attempt and the whole SpeCa
+trajectory with the CPU oracle, through the C ABI.
+
+Bars: accept/reject decisions and schedules equal (both sides take the decision in
+fp32 on the same fp32 thresholds; the smallest relative margin |e - tau| / tau is
+printed so that a decision inside rounding noise would be visible);
+final latents max-abs error / max-abs value <= 1e-5 for fp32 models and <= 2e-2 for
+bf16 models."""
+import numpy as np
+import pytest
+
+import speca_inputs as si
+from oracle import dit as odit, sampler as osamp, speca_core as core
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def max_abs_rel(a, b):
+    a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
+    return float(np.max(np.abs(a - b)) / max(np.max(np.abs(b)), 1e-30))
+
+
+def make_gpu(shape, weights):
+    import paper_2509_11628_amd as sp
+    from paper_2509_11628_amd import binding as bd
+    dt = bd.BF16 if shape.dtype == "bf16" else bd.F32
+    return sp.Context(sp.dit_desc(shape), sp.to_device(weights, dt))
+
+
+@pytest.fixture(scope="module", params=["f32", "bf16"])
+def tiny(request):
+    s = si.dit_tiny(request.param)
+    w = si.make_dit_weights(s, 0)
+    return s, w, odit.DiTOracle(s, w), make_gpu(s, w)
+
+
+def _tol(s):
+    return 1e-5 if s.dtype == "f32" else 2e-2
+
+
+def test_full_step_matches_oracle_forward(tiny):
+    import paper_2509_11628_amd as sp
+    s, w, om, ctx = tiny
+    B = 3
+    x = si.make_latents(B, s.in_channels, s.latent_hw, seed=5)
+    labels = [1, 7, s.num_classes]
+    ctx.init_cache(sp.make_cfg(order=1, interval=4), B)
+    xd = torch.from_numpy(x).cuda()
+    out = torch.zeros_like(xd)
+    ctx.full_step(xd, 0, [0, 1, 2], out, labels=labels, timestep=640.0)
+    exp, feats = om.forward(x, 640.0, labels)
+    assert max_abs_rel(out.cpu().numpy(), exp) <= _tol(s)
+    # the cache now holds every slot's feature: an order-0 forecast returns it
+    td = torch.bfloat16 if s.dtype == "bf16" else torch.float32
+    f = torch.empty((s.n_slots, B, s.tokens, s.hidden), dtype=td, device="cuda")
+    ctx.forecast(1, [0, 1, 2], f)
+    got = f.float().cpu().numpy()
+    for j in range(s.n_slots):
+        assert max_abs_rel(got[j], feats[j]) <= (1e-5 if s.dtype == "f32" else 1.5e-2), j
+    # a row's result does not depend on which other rows share the launch (bitwise)
+    out1 = torch.zeros_like(xd)
+    ctx.init_cache(sp.make_cfg(order=1, interval=4), B)
+    ctx.full_step(xd, 0, [1], out1, labels=labels, timestep=640.0)
+    assert torch.equal(out1[1], out[1]) and float(out1[0].abs().max()) == 0.0
+
+
+def test_spec_step_matches_oracle(tiny):
+    import paper_2509_11628_amd as sp
+    s, w, om, ctx = tiny
+    B = 2
+    x = si.make_latents(B, s.in_channels, s.latent_hw, seed=6)
+    labels = [3, 4]
+    cfg = osamp.SpecaConfig(order=1, interval=8)
+    ctx.init_cache(sp.make_cfg(order=1, interval=8), B)
+    xd = torch.from_numpy(x).cuda()
+    out = torch.zeros_like(xd)
+    store = "bf16" if s.dtype == "bf16" else None
+    caches = [core.FeatureCache(om.n_slots, 1, "taylor", store) for _ in range(B)]
+    # the latent moves between steps (as it does along a trajectory), so the features really change:
+    # the verification error is then well above the ~3e-3 noise floor that bf16 activations add (in quadrature)
+    drift = si.make_latents(B, s.in_channels, s.latent_hw, seed=60)
+    xs = {0: x, 2: (x + 0.2 * drift).astype(np.float32), 3: (x + np.array([0.6, 1.2], np.float32)[:, None, None, None] * drift).astype(np.float32)}
+    for step, t in ((0, 900.0), (2, 800.0)):
+        xd = torch.from_numpy(xs[step]).cuda()
+        ctx.full_step(xd, step, [0, 1], out, labels=labels, timestep=t)
+        for b in range(B):
+            osamp.full_step(om, caches[b], xs[step][b:b + 1], t, labels[b:b + 1], step)
+    exp_e, exp_out = [], []
+    x = xs[3]
+    xd = torch.from_numpy(x).cuda()
+    for b in range(B):
+        ok, e, o = osamp.speculative_attempt(om, caches[b], cfg, x[b:b + 1], 750.0, labels[b:b + 1], 3, np.float32(np.inf))
+        exp_e.append(float(e[0])); exp_out.append(o[0])
+    print(f"\n[{s.dtype}] expected verification errors {exp_e}")
+    err, acc = ctx.spec_step(xd, 3, [0, 1], np.inf, out, labels=labels, timestep=750.0)
+    np.testing.assert_allclose(err, exp_e, rtol=1e-4 if s.dtype == "f32" else 1e-1)
+    assert acc.tolist() == [True, True]
+    assert max_abs_rel(out.cpu().numpy(), np.stack(exp_out)) <= _tol(s)
+    # a threshold between the two errors accepts exactly the smaller one
+    mid = float(np.sqrt(exp_e[0] * exp_e[1]))
+    if abs(exp_e[0] - exp_e[1]) / mid > 0.2:
+        _, acc2 = ctx.spec_step(xd, 3, [0, 1], mid, out, labels=labels, timestep=750.0)
+        assert acc2.tolist() == [e <= mid for e in exp_e]
+
+
+def _run_both(s, om, ctx, S, B, cfg_kwargs, tau, cfg_scale=0.0, seed=0):
+    import paper_2509_11628_amd as sp
+    from paper_2509_11628_amd import binding as bd
+    ts, ab = si.ddim_tables(S)
+    lat = si.make_latents(B, s.in_channels, s.latent_hw, seed)
+    lab = si.make_labels(B, s.num_classes, seed)
+    sol = osamp.Solver("ddim", ts, ab, cfg_scale)
+    exp, tr = osamp.sample(om, osamp.SpecaConfig(cache_store="bf16" if s.dtype == "bf16" else None, **cfg_kwargs), sol, tau, lat, lab)
+    mode = bd.COEF_NEWTON if cfg_kwargs.get("mode") == "newton" else bd.COEF_TAYLOR
+    kw = {k: v for k, v in cfg_kwargs.items() if k != "mode"}
+    ctx.init_cache(sp.make_cfg(coef_mode=mode, **kw), B * (2 if cfg_scale > 0 else 1))
+    xd = torch.from_numpy(lat).cuda()
+    got = ctx.sample(xd, ts, ab, tau, cfg_scale=cfg_scale, labels=lab)
+    return exp, tr, xd.cpu().numpy(), got
+
+
+def _margin(tr):
+    e = np.nanmax(tr.err, axis=2)
+    with np.errstate(invalid="ignore"):
+        m = np.abs(e - tr.tau[None, :]) / tr.tau[None, :]
+    return float(np.nanmin(m)) if np.any(np.isfinite(m)) else float("inf")
+
+
+# Noise the device path adds to the verification error, in quadrature: fp32 rounding for
+# fp32 models; for bf16 models the bf16 rounding of activations (~3e-3) and of the cached
+# differences, which a second-order extrapolation amplifies to ~1e-2.
+NOISE = {"f32": 1e-5, "bf16": 1.2e-2}
+
+
+def compare_traces(tr, gtr, dtype):
+    """Schedules must agree decision by decision.  A decision whose oracle error is closer to
+    the threshold than the device noise may legitimately flip; from there on that sample's
+    trajectory is a different (equally valid) one and is no longer compared.
+    -> (number of decisions compared, True if every sample agreed to the end)."""
+    n, B, S = NOISE[dtype], tr.kind.shape[0], tr.kind.shape[1]
+    compared, complete = 0, True
+    for b in range(B):
+        for s in range(S):
+            ko, kg = int(tr.kind[b, s]), int(gtr["kind"][b, s])
+            verified = not np.all(np.isnan(tr.err[b, s]))
+            if verified:
+                e, tau = float(np.nanmax(tr.err[b, s])), float(tr.tau[s])
+                decisive = e > tau * 1.02 + 1e-7 or np.sqrt(e * e + n * n) < tau * 0.98
+            else:
+                decisive = True
+            if ko != kg:
+                assert not decisive, f"sample {b} step {s}: oracle kind {ko} (e={tr.err[b, s]}, tau={tr.tau[s]}) vs device {kg} (e={gtr['err'][b, s]})"
+                complete = False
+                break
+            if verified:
+                compared += 1
+                ge = float(np.nanmax(gtr["err"][b, s]))
+                assert abs(ge - e) <= (1e-3 * e + 1e-6 if dtype == "f32" else 0.1 * e + n), (b, s, ge, e)
+    return compared, complete
+
+
+def test_config1_trajectory(tiny):
+    """Configuration 1: 20 DDIM steps, order 1, interval 4, verify = last block, tau 0.05 -> 0.01 linear."""
+    s, w, om, ctx = tiny
+    tau = core.tau_linear(0.05, 0.01, 20)
+    exp, tr, got, gtr = _run_both(s, om, ctx, 20, 2, dict(order=1, interval=4), tau)
+    print(f"\n[{s.dtype}] min decision margin {_margin(tr):.3e}; kinds {tr.kind.tolist()}")
+    compared, complete = compare_traces(tr, gtr, s.dtype)
+    print(f"decisions compared {compared}, schedules identical to the end: {complete}")
+    assert compared >= 10
+    if s.dtype == "f32":
+        assert complete
+    if complete:
+        assert max_abs_rel(got, exp) <= _tol(s)
+        assert gtr["n_full"] == tr.n_full and gtr["n_reject"] == int((tr.kind == 2).sum())
+    assert (tr.kind == 1).sum() > 0 and (tr.kind == 2).sum() > 0     # both paths exercised
+
+
+def test_config1_geometric_and_newton(tiny):
+    s, w, om, ctx = tiny
+    tau = core.tau_geometric(0.05, 0.2, 20)
+    for kw in (dict(order=1, interval=4), dict(order=2, interval=5, mode="newton"), dict(order=2, interval=5, verify_block=0)):
+        exp, tr, got, gtr = _run_both(s, om, ctx, 20, 2, kw, tau)
+        compared, complete = compare_traces(tr, gtr, s.dtype)
+        assert compared >= 6, kw
+        if s.dtype == "f32":
+            assert complete, kw
+        if complete:
+            assert max_abs_rel(got, exp) <= _tol(s), kw
+
+
+def test_threshold_zero_is_plain_sampling(tiny):
+    s, w, om, ctx = tiny
+    tau = np.zeros(20, np.float32)
+    exp, tr, got, gtr = _run_both(s, om, ctx, 20, 2, dict(order=1, interval=4), tau)
+    assert np.all(gtr["kind"] == 0) and gtr["n_spec"] == 0
+    ts, ab = si.ddim_tables(20)
+    plain = osamp.sample_plain(om, osamp.Solver("ddim", ts, ab), si.make_latents(2, s.in_channels, s.latent_hw, 0),
+                               si.make_labels(2, s.num_classes, 0))
+    assert max_abs_rel(got, plain) <= _tol(s)
+    # and the library's own tau=0 run is bit-identical to a second run (deterministic kernels)
+    _, _, got2, _ = _run_both(s, om, ctx, 20, 2, dict(order=1, interval=4), tau)
+    assert got.tobytes() == got2.tobytes()
+
+
+def test_threshold_infinite_gives_fixed_pattern(tiny):
+    s, w, om, ctx = tiny
+    tau = np.full(12, np.inf, np.float32)
+    exp, tr, got, gtr = _run_both(s, om, ctx, 12, 2, dict(order=2, interval=4), tau)
+    assert gtr["kind"][0].tolist() == [0 if i % 4 == 0 else 1 for i in range(12)]
+    assert max_abs_rel(got, exp) <= _tol(s)
+
+
+def test_guided_trajectory(tiny):
+    s, w, om, ctx = tiny
+    tau = core.tau_linear(0.08, 0.02, 10)
+    exp, tr, got, gtr = _run_both(s, om, ctx, 10, 3, dict(order=1, interval=3), tau, cfg_scale=1.5, seed=2)
+    print(f"\n[{s.dtype}] guided: min margin {_margin(tr):.3e}; kinds {tr.kind.tolist()}")
+    compared, complete = compare_traces(tr, gtr, s.dtype)
+    assert compared >= 6
+    if s.dtype == "f32":
+        assert complete
+    if complete:
+        assert max_abs_rel(got, exp) <= _tol(s)
+        m = ~np.isnan(tr.err)
+        assert np.array_equal(~np.isnan(gtr["err"]), m)
+        np.testing.assert_allclose(gtr["err"][m], tr.err[m], rtol=1e-3 if s.dtype == "f32" else 1.5e-1, atol=0 if s.dtype == "f32" else 5e-3)
+
+
+def test_sample_error_paths(tiny):
+    import paper_2509_11628_amd as sp
+    from paper_2509_11628_amd import binding as bd
+    s, w, om, ctx = tiny
+    ts, ab = si.ddim_tables(4)
+    x = torch.zeros((2, s.in_channels, s.latent_hw, s.latent_hw), device="cuda")
+    ctx.init_cache(sp.make_cfg(order=1, interval=2), 2)
+    with pytest.raises(sp.SpecaError) as e:
+        ctx.sample(x, ts, ab, np.ones(4, np.float32), cfg_scale=1.5, labels=[0, 1])     # needs 4 rows
+    assert e.value.code == bd.ESTATE
+    with pytest.raises(sp.SpecaError) as e:
+        ctx.sample(x, ts, ab, np.ones(4, np.float32), labels=[0, 99])
+    assert e.value.code == bd.EINVAL
+    with pytest.raises(sp.SpecaError) as e:
+        ctx.init_cache(sp.make_cfg(order=1, interval=2, verify_block=5), 2)
+    assert e.value.code == bd.EINVAL
