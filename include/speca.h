@@ -205,6 +205,44 @@ int speca_spec_step(speca_ctx* ctx, const void* x, const speca_cond* cond, int s
 int speca_sample(speca_ctx* ctx, void* latents_inout, int batch, const speca_cond* cond,
                  const speca_solver* solver, const float* tau, speca_trace* trace_out);
 
+
+/* ---- the dense contractions of the reference step, callable on their own ------------------- */
+
+/* out[m][n] = act(sum_k a[m][k] w[n][k] + bias[n]) on DEVICE tensors of type dtype (a: [m][k],
+ * w: [n][k], bias: [n] or NULL, out: [m][n]); act 0 = none, 1 = GELU (tanh form), 2 = SiLU;
+ * fp32 accumulation.  These are the QKV / out-proj / MLP GEMMs of a block (Sec. 3.1.2) at
+ * whatever shape the caller gives; n must be a multiple of 4.  Asynchronous on hip_stream.
+ * Errors: message via speca_last_error(NULL). */
+int speca_linear(void* hip_stream, int dtype, const void* a, int m, int k, const void* w, int n, const void* bias, int act,
+                 void* out);
+/* out = softmax(q k^T / sqrt(head_dim)) v without mask; qkv: DEVICE [rows][tokens][3][heads][head_dim],
+ * out: DEVICE [rows][tokens][heads*head_dim], both of type dtype.  Asynchronous on hip_stream. */
+int speca_attention(void* hip_stream, int dtype, const void* qkv, void* out, int rows, int tokens, int heads, int head_dim);
+
+/* ---- measurement ----------------------------------------------------------------------------- */
+
+/* Kernel classes of the per-class timing below. */
+enum { SPECA_PROF_GEMM = 0,      /* QKV / out-proj / FC1 / FC2 contractions of the blocks */
+       SPECA_PROF_ATTENTION = 1,
+       SPECA_PROF_FORECAST = 2,  /* Eq. 2: materialised forecast or forecast-and-fold */
+       SPECA_PROF_VERIFY = 3,    /* Eq. 4 reductions */
+       SPECA_PROF_REFRESH = 4,   /* stand-alone Eq. 3 refresh (the fused one is part of GEMM time) */
+       SPECA_PROF_OTHER = 5,     /* conditioning, modulation GEMM, LayerNorm, embed, final layer, solver */
+       SPECA_PROF_CLASSES = 6 };
+
+typedef struct speca_profile {
+  int64_t launches[SPECA_PROF_CLASSES];
+  double  ms[SPECA_PROF_CLASSES];      /* sum of HIP-event durations on the context's stream */
+  double  flops[SPECA_PROF_CLASSES];   /* algorithmic: 2 per multiply-add of the contraction */
+  double  bytes[SPECA_PROF_CLASSES];   /* algorithmic: tensors the method must read + write once */
+} speca_profile;
+
+/* While a profile is open every kernel launch of the context is bracketed by a HIP event pair
+ * on its stream (this serialises launches and costs a few microseconds each: time a workload
+ * for throughput with the profile closed).  speca_profile_end synchronises and sums. */
+int speca_profile_begin(speca_ctx* ctx);
+int speca_profile_end(speca_ctx* ctx, speca_profile* out);
+
 /* ---- host-only helpers (no device work; usable without a GPU) ----------------------------- */
 
 /* tau[s] = tau0 * beta^(s/S)   (Sec. 3.4.2 adaptive threshold, progress (T-t)/T = s/S). */

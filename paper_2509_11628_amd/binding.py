@@ -63,6 +63,12 @@ class Trace(C.Structure):
                 ("n_full", C.c_int32), ("n_spec", C.c_int32), ("n_reject", C.c_int32)]
 
 
+class Profile(C.Structure):
+    _fields_ = [("launches", C.c_int64 * 6), ("ms", C.c_double * 6), ("flops", C.c_double * 6), ("bytes", C.c_double * 6)]
+
+
+PROF_CLASSES = ["gemm", "attention", "forecast", "verify", "refresh", "other"]
+
 _lib = None
 
 
@@ -89,6 +95,10 @@ def load_library() -> C.CDLL:
         "speca_verify": [vp, vp, vp, C.c_int, C.c_int64, C.c_int, f32p, C.c_float, f32p, u8p],
         "speca_spec_step": [vp, vp, C.POINTER(Cond), C.c_int, i32p, C.c_int, f32p, C.c_int, f32p, u8p, vp],
         "speca_sample": [vp, vp, C.c_int, C.POINTER(Cond), C.POINTER(Solver), f32p, C.POINTER(Trace)],
+        "speca_linear": [vp, C.c_int, vp, C.c_int, C.c_int, vp, C.c_int, vp, C.c_int, vp],
+        "speca_attention": [vp, C.c_int, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int],
+        "speca_profile_begin": [vp],
+        "speca_profile_end": [vp, C.POINTER(Profile)],
         "speca_tau_geometric": [C.c_float, C.c_float, C.c_int, f32p],
         "speca_tau_linear": [C.c_float, C.c_float, C.c_int, f32p],
         "speca_coefficients": [C.c_int, C.c_int, i32p, C.c_int, C.c_int, f32p],
@@ -111,6 +121,7 @@ def load_library() -> C.CDLL:
 
 EXPORTED = ["speca_create", "speca_destroy", "speca_last_error", "speca_init_cache", "speca_refresh",
             "speca_full_step", "speca_forecast", "speca_verify", "speca_spec_step", "speca_sample",
+            "speca_linear", "speca_attention", "speca_profile_begin", "speca_profile_end",
             "speca_tau_geometric", "speca_tau_linear", "speca_coefficients", "speca_divisors",
             "speca_sched_create", "speca_sched_destroy", "speca_sched_plan", "speca_sched_commit",
             "speca_sched_refs"]
@@ -166,6 +177,41 @@ def _check(ctx, code: int):
     if code != OK:
         msg = load_library().speca_last_error(ctx).decode() if ctx is not None else ""
         raise SpecaError(code, msg)
+
+
+def linear(a, w, bias=None, act: int = 0, out=None):
+    """speca_linear on torch device tensors: a [M,K], w [N,K] -> [M,N]."""
+    import torch
+    lib = load_library()
+    M, K = a.shape
+    N = w.shape[0]
+    assert w.shape[1] == K and a.is_contiguous() and w.is_contiguous() and a.dtype == w.dtype
+    if out is None:
+        out = torch.empty((M, N), dtype=a.dtype, device=a.device)
+    dt = BF16 if a.dtype == torch.bfloat16 else F32
+    code = lib.speca_linear(C.c_void_p(torch.cuda.current_stream().cuda_stream), dt, C.c_void_p(a.data_ptr()), M, K,
+                            C.c_void_p(w.data_ptr()), N, C.c_void_p(bias.data_ptr()) if bias is not None else None, act,
+                            C.c_void_p(out.data_ptr()))
+    if code != OK:
+        raise SpecaError(code, lib.speca_last_error(None).decode())
+    return out
+
+
+def attention(qkv, heads: int, out=None):
+    """speca_attention on a torch device tensor qkv [rows, T, 3*H*hd] -> [rows, T, H*hd]."""
+    import torch
+    lib = load_library()
+    rows, T, D3 = qkv.shape
+    D = D3 // 3
+    assert qkv.is_contiguous() and D % heads == 0
+    if out is None:
+        out = torch.empty((rows, T, D), dtype=qkv.dtype, device=qkv.device)
+    dt = BF16 if qkv.dtype == torch.bfloat16 else F32
+    code = lib.speca_attention(C.c_void_p(torch.cuda.current_stream().cuda_stream), dt, C.c_void_p(qkv.data_ptr()),
+                               C.c_void_p(out.data_ptr()), rows, T, heads, D // heads)
+    if code != OK:
+        raise SpecaError(code, lib.speca_last_error(None).decode())
+    return out
 
 
 class Scheduler:
@@ -278,6 +324,15 @@ class Context:
         self._ck(self.lib.speca_verify(self.h, C.c_void_p(pred.data_ptr()), C.c_void_p(truth.data_ptr()), n_rows, E, dtype,
                                        _p(t, C.c_float) if t is not None else None, eps, _p(err, C.c_float), _p(acc, C.c_uint8)))
         return err, (acc.astype(bool) if t is not None else None)
+
+    def profile_begin(self):
+        self._ck(self.lib.speca_profile_begin(self.h))
+
+    def profile_end(self) -> Dict[str, dict]:
+        p = Profile()
+        self._ck(self.lib.speca_profile_end(self.h, C.byref(p)))
+        return {name: {"launches": int(p.launches[i]), "ms": float(p.ms[i]), "flops": float(p.flops[i]), "bytes": float(p.bytes[i])}
+                for i, name in enumerate(PROF_CLASSES)}
 
     def _cond(self, labels=None, timestep: float = 0.0, txt=None, pooled=None):
         lab = _i32(labels) if labels is not None else None

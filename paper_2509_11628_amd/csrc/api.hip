@@ -5,6 +5,7 @@
 #include <new>
 
 #include "context.h"
+#include "gemm.h"
 #include "kernels.h"
 #include "model.h"
 
@@ -195,7 +196,12 @@ static Error refresh_impl(speca_ctx* ctx, int step, const int32_t* rows, int n_r
   if (n_rows > kMaxRows) SPECA_FAIL(SPECA_EUNSUPPORTED, "speca_refresh takes at most %d rows per call", kMaxRows);
   RowTable rt;
   SPECA_TRY(build_refresh_table(ctx, step, rows, n_rows, &rt));
-  SPECA_TRY(launch_refresh(ctx->geom, rt, features, ctx->stream));
+  {
+    // reads the new feature and the old differences below the new order, writes the new differences
+    const double esz = dtype_size(ctx->geom.dtype);
+    ProfScope ps(ctx, SPECA_PROF_REFRESH, 0.0, ctx->geom.n_slots * ctx->geom.E * esz * (2.0 * table_tensors(rt)));
+    SPECA_TRY(launch_refresh(ctx->geom, rt, features, ctx->stream));
+  }
   push_refs(ctx, step, rows, n_rows);
   return ok();
 }
@@ -207,6 +213,8 @@ static Error forecast_impl(speca_ctx* ctx, int step, const int32_t* rows, int n_
   if (n_rows > kMaxRows) SPECA_FAIL(SPECA_EUNSUPPORTED, "speca_forecast takes at most %d rows per call", kMaxRows);
   RowTable rt;
   SPECA_TRY(build_forecast_table(ctx, step, rows, n_rows, &rt));
+  const double esz = dtype_size(ctx->geom.dtype);
+  ProfScope ps(ctx, SPECA_PROF_FORECAST, 0.0, ctx->geom.n_slots * ctx->geom.E * esz * (table_tensors(rt) + rt.n));
   return launch_forecast(ctx->geom, rt, out, ctx->stream);
 }
 
@@ -230,8 +238,11 @@ static Error verify_impl(speca_ctx* ctx, const void* pred, const void* truth, in
     }
     const char* p = static_cast<const char*>(pred) + static_cast<size_t>(r0) * E * esz;
     const char* t = static_cast<const char*>(truth) + static_cast<size_t>(r0) * E * esz;
-    SPECA_TRY(launch_verify(metric, p, dtype, t, dtype, E, nullptr, nullptr, 0, n, eps, tau ? v.tau_dev : nullptr, v.partial,
-                            v.err_dev, v.acc_dev, ctx->stream));
+    {
+      ProfScope ps(ctx, SPECA_PROF_VERIFY, 0.0, 2.0 * n * E * esz);
+      SPECA_TRY(launch_verify(metric, p, dtype, t, dtype, E, nullptr, nullptr, 0, n, eps, tau ? v.tau_dev : nullptr, v.partial,
+                              v.err_dev, v.acc_dev, ctx->stream));
+    }
     SPECA_HIP(hipMemcpyAsync(v.h_err, v.err_dev, n * sizeof(float), hipMemcpyDeviceToHost, ctx->stream));
     if (tau) SPECA_HIP(hipMemcpyAsync(v.h_acc, v.acc_dev, n, hipMemcpyDeviceToHost, ctx->stream));
     SPECA_HIP(hipStreamSynchronize(ctx->stream));
@@ -344,6 +355,52 @@ int speca_spec_step(speca_ctx* ctx, const void* x, const speca_cond* cond, int s
                     const float* tau_per_row, int pair_stride, float* err_out, uint8_t* accept_out, void* model_out) {
   if (!ctx) return SPECA_EINVAL;
   return finish(ctx, spec_step_impl(ctx, x, cond, step, rows, n_rows, tau_per_row, pair_stride, err_out, accept_out, model_out));
+}
+
+int speca_linear(void* hip_stream, int dtype, const void* a, int m, int k, const void* w, int n, const void* bias, int act,
+                 void* out) {
+  if (dtype != SPECA_F32 && dtype != SPECA_BF16) { g_create_error = "dtype"; return SPECA_EINVAL; }
+  if (!a || !w || !out || m < 1 || n < 1 || k < 1 || act < 0 || act > 2) { g_create_error = "speca_linear: bad argument"; return SPECA_EINVAL; }
+  GemmEpi e;
+  e.mode = act == 1 ? EPI_GELU : act == 2 ? EPI_SILU : EPI_STORE;
+  e.bias = bias; e.out = out; e.ldo = n;
+  Error r = launch_gemm(dtype, a, k, w, k, m, n, k, e, static_cast<hipStream_t>(hip_stream));
+  if (r.code != SPECA_OK) g_create_error = r.msg;
+  return r.code;
+}
+
+int speca_attention(void* hip_stream, int dtype, const void* qkv, void* out, int rows, int tokens, int heads, int head_dim) {
+  if (dtype != SPECA_F32 && dtype != SPECA_BF16) { g_create_error = "dtype"; return SPECA_EINVAL; }
+  Error r = launch_attention(dtype, qkv, out, rows, tokens, heads, head_dim, static_cast<hipStream_t>(hip_stream));
+  if (r.code != SPECA_OK) g_create_error = r.msg;
+  return r.code;
+}
+
+int speca_profile_begin(speca_ctx* ctx) {
+  if (!ctx) return SPECA_EINVAL;
+  for (auto& r : ctx->prof.recs) { ctx->prof.pool.push_back(r.a); ctx->prof.pool.push_back(r.b); }
+  ctx->prof.recs.clear();
+  ctx->prof.on = true;
+  return SPECA_OK;
+}
+
+int speca_profile_end(speca_ctx* ctx, speca_profile* out) {
+  if (!ctx || !out) return SPECA_EINVAL;
+  ctx->prof.on = false;
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) { ctx->err = "hipStreamSynchronize failed"; return SPECA_EHIP; }
+  std::memset(out, 0, sizeof(*out));
+  for (auto& r : ctx->prof.recs) {
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) { ctx->err = "hipEventElapsedTime failed"; return SPECA_EHIP; }
+    out->launches[r.cls] += 1;
+    out->ms[r.cls] += ms;
+    out->flops[r.cls] += r.flops;
+    out->bytes[r.cls] += r.bytes;
+    ctx->prof.pool.push_back(r.a);
+    ctx->prof.pool.push_back(r.b);
+  }
+  ctx->prof.recs.clear();
+  return SPECA_OK;
 }
 
 int speca_sample(speca_ctx* ctx, void* latents_inout, int batch, const speca_cond* cond, const speca_solver* solver,

@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "common.h"
+#include "profile.h"
 #include "sched.h"
 
 namespace speca {
@@ -43,11 +44,24 @@ struct speca_ctx {
 
   speca::VerifyScratch vs;
   std::unique_ptr<speca::Model> model;
+  speca::Profiler prof;
 
   int64_t elems_per_slot_row() const { return geom.E; }
 };
 
 namespace speca {
+
+// Brackets the launches made in its scope with an event pair when a profile is open.
+struct ProfScope {
+  speca_ctx* c;
+  ProfScope(speca_ctx* ctx, int cls, double flops, double bytes) : c(ctx) { c->prof.begin(cls, flops, bytes, c->stream); }
+  ~ProfScope() { c->prof.end(c->stream); }
+};
+inline double table_tensors(const RowTable& rt) {   // sum over rows of (order + 1)
+  double t = 0;
+  for (int i = 0; i < rt.n; ++i) t += rt.order[i] + 1;
+  return t;
+}
 
 // Fill a RowTable with forecast coefficients for rows[0..n) at `step` (Eq. 2).
 Error build_forecast_table(const speca_ctx* ctx, int step, const int32_t* rows, int n, RowTable* rt);

@@ -88,7 +88,9 @@ struct DiT final : Model {
   }
 
   // conditioning + modulation of all blocks for compact rows 0..n-1 (labels of rows[i])
-  Error conditioning(hipStream_t st, float t, const int32_t* labels_per_row, const int32_t* rows, int n) {
+  Error conditioning(speca_ctx* ctx, float t, const int32_t* labels_per_row, const int32_t* rows, int n) {
+    hipStream_t st = ctx->stream;
+    ProfScope ps(ctx, SPECA_PROF_OTHER, 2.0 * n * D * (d.freq_dim + D + static_cast<double>(mod_n)), static_cast<double>(mod_n) * D * esz);
     RowLabels lab{};
     for (int i = 0; i < n; ++i) lab.v[i] = labels_per_row[rows[i]];
     SPECA_TRY(launch_sinusoid(d.dtype, emb, n, d.freq_dim, t, st));
@@ -105,7 +107,9 @@ struct DiT final : Model {
     return ok();
   }
 
-  Error embed(hipStream_t st, const float* x, int x_mod, const int32_t* rows, int n) {
+  Error embed(speca_ctx* ctx, const float* x, int x_mod, const int32_t* rows, int n) {
+    hipStream_t st = ctx->stream;
+    ProfScope ps(ctx, SPECA_PROF_OTHER, 0.0, static_cast<double>(n) * T * D * 4);
     RowLabels xr{};
     for (int i = 0; i < n; ++i) xr.v[i] = rows[i] % x_mod;
     return launch_patch_embed(d.dtype, x, xr, patch_w, patch_b, pos, h, n, d.in_channels, d.latent_h, d.latent_w, d.patch, D, st);
@@ -117,14 +121,25 @@ struct DiT final : Model {
   Error attn_branch(speca_ctx* ctx, int l, float* hs, int n, const RowTable* refresh_rt) {
     hipStream_t st = ctx->stream;
     const int64_t M = static_cast<int64_t>(n) * T;
-    SPECA_TRY(launch_ln_modulate(d.dtype, hs, mod_at(l, 0), mod_at(l, 1), mod_n, xn, M, T, D, st));
+    const double Md = static_cast<double>(M);
+    {
+      ProfScope ps(ctx, SPECA_PROF_OTHER, 0.0, Md * D * (4 + esz));
+      SPECA_TRY(launch_ln_modulate(d.dtype, hs, mod_at(l, 0), mod_at(l, 1), mod_n, xn, M, T, D, st));
+    }
     GemmEpi e;
     e.mode = EPI_STORE; e.bias = blk[l].qkv_b; e.out = qkv; e.ldo = 3 * D;
-    SPECA_TRY(launch_gemm(d.dtype, xn, D, blk[l].qkv_w, D, static_cast<int>(M), 3 * D, D, e, st));
-    SPECA_TRY(launch_attention(d.dtype, qkv, att, n, T, H, hd, st));
+    {
+      ProfScope ps(ctx, SPECA_PROF_GEMM, 2.0 * Md * 3 * D * D, (Md * 4 * D + 3.0 * D * D) * esz);
+      SPECA_TRY(launch_gemm(d.dtype, xn, D, blk[l].qkv_w, D, static_cast<int>(M), 3 * D, D, e, st));
+    }
+    {
+      ProfScope ps(ctx, SPECA_PROF_ATTENTION, 4.0 * n * H * static_cast<double>(T) * T * hd, Md * 4 * D * esz);
+      SPECA_TRY(launch_attention(d.dtype, qkv, att, n, T, H, hd, st));
+    }
     GemmEpi b;
     b.mode = EPI_BRANCH; b.bias = blk[l].proj_b; b.h = hs; b.ldh = D; b.gate = mod_at(l, 2); b.gate_stride = mod_n; b.tokens = T;
     if (refresh_rt) { b.refresh = 1; b.slot = 2 * l; b.g = ctx->geom; b.rt = *refresh_rt; }
+    ProfScope ps(ctx, SPECA_PROF_GEMM, 2.0 * Md * D * D, (Md * D + 1.0 * D * D) * esz + Md * D * 8);
     SPECA_TRY(launch_gemm(d.dtype, att, D, blk[l].proj_w, D, static_cast<int>(M), D, D, b, st));
     return ok();
   }
@@ -133,10 +148,17 @@ struct DiT final : Model {
   Error mlp_branch(speca_ctx* ctx, int l, float* hs, int n, const RowTable* refresh_rt, float* truth_out) {
     hipStream_t st = ctx->stream;
     const int64_t M = static_cast<int64_t>(n) * T;
-    SPECA_TRY(launch_ln_modulate(d.dtype, hs, mod_at(l, 3), mod_at(l, 4), mod_n, xn, M, T, D, st));
+    const double Md = static_cast<double>(M);
+    {
+      ProfScope ps(ctx, SPECA_PROF_OTHER, 0.0, Md * D * (4 + esz));
+      SPECA_TRY(launch_ln_modulate(d.dtype, hs, mod_at(l, 3), mod_at(l, 4), mod_n, xn, M, T, D, st));
+    }
     GemmEpi e;
     e.mode = EPI_GELU; e.bias = blk[l].fc1_b; e.out = f1; e.ldo = Dm;
-    SPECA_TRY(launch_gemm(d.dtype, xn, D, blk[l].fc1_w, D, static_cast<int>(M), Dm, D, e, st));
+    {
+      ProfScope ps(ctx, SPECA_PROF_GEMM, 2.0 * Md * Dm * D, (Md * (D + Dm) + 1.0 * D * Dm) * esz);
+      SPECA_TRY(launch_gemm(d.dtype, xn, D, blk[l].fc1_w, D, static_cast<int>(M), Dm, D, e, st));
+    }
     GemmEpi b;
     b.bias = blk[l].fc2_b;
     if (truth_out) {
@@ -145,6 +167,7 @@ struct DiT final : Model {
       b.mode = EPI_BRANCH; b.h = hs; b.ldh = D; b.gate = mod_at(l, 5); b.gate_stride = mod_n; b.tokens = T;
       if (refresh_rt) { b.refresh = 1; b.slot = 2 * l + 1; b.g = ctx->geom; b.rt = *refresh_rt; }
     }
+    ProfScope ps(ctx, SPECA_PROF_GEMM, 2.0 * Md * Dm * D, (Md * Dm + 1.0 * D * Dm) * esz + Md * D * 8);
     SPECA_TRY(launch_gemm(d.dtype, f1, Dm, blk[l].fc2_w, Dm, static_cast<int>(M), D, Dm, b, st));
     return ok();
   }
@@ -153,6 +176,7 @@ struct DiT final : Model {
     hipStream_t st = ctx->stream;
     const int64_t M = static_cast<int64_t>(n) * T;
     const float* fm = mod + static_cast<int64_t>(L) * 6 * D;
+    ProfScope ps(ctx, SPECA_PROF_OTHER, 2.0 * M * Kp * D, static_cast<double>(M) * D * (4 + 2 * esz));
     SPECA_TRY(launch_ln_modulate(d.dtype, hs, fm, fm + D, mod_n, xn, M, T, D, st));
     GemmEpi e;
     e.mode = EPI_F32; e.bias = final_b; e.out = tok; e.ldo = Kp;
@@ -167,8 +191,8 @@ struct DiT final : Model {
     if (n > cap_rows) SPECA_FAIL(SPECA_EUNSUPPORTED, "at most %d rows per launch", cap_rows);
     RowTable rt;
     SPECA_TRY(build_refresh_table(ctx, step, rows, n, &rt));
-    SPECA_TRY(conditioning(ctx->stream, cond->timestep, labels_per_row, rows, n));
-    SPECA_TRY(embed(ctx->stream, x, x_mod, rows, n));
+    SPECA_TRY(conditioning(ctx, cond->timestep, labels_per_row, rows, n));
+    SPECA_TRY(embed(ctx, x, x_mod, rows, n));
     for (int l = 0; l < L; ++l) {
       SPECA_TRY(attn_branch(ctx, l, h, n, &rt));
       SPECA_TRY(mlp_branch(ctx, l, h, n, &rt, nullptr));
@@ -197,12 +221,19 @@ struct DiT final : Model {
       }
     }
     const int lv = ctx->cfg.verify_block >= 0 ? ctx->cfg.verify_block : L - 1;
-    SPECA_TRY(conditioning(st, cond->timestep, labels_per_row, rows, n));
-    SPECA_TRY(embed(st, x, x_mod, rows, n));
+    SPECA_TRY(conditioning(ctx, cond->timestep, labels_per_row, rows, n));
+    SPECA_TRY(embed(ctx, x, x_mod, rows, n));
     // Eq. 2 for every slot before the verify block, folded into h
-    SPECA_TRY(launch_forecast_fold(ctx->geom, rt, h, h, mod, mod_n, gate_off_dev, 0, 2 * lv, D, st));
+    const double tens = table_tensors(rt), Ed = static_cast<double>(ctx->geom.E);
+    {
+      ProfScope ps(ctx, SPECA_PROF_FORECAST, 0.0, 2.0 * lv * tens * Ed * esz + 2.0 * n * Ed * 4);
+      SPECA_TRY(launch_forecast_fold(ctx->geom, rt, h, h, mod, mod_n, gate_off_dev, 0, 2 * lv, D, st));
+    }
     // accepted path: forecasts for the verify block and everything after it -> h2
-    SPECA_TRY(launch_forecast_fold(ctx->geom, rt, h, h2, mod, mod_n, gate_off_dev, 2 * lv, 2 * L, D, st));
+    {
+      ProfScope ps(ctx, SPECA_PROF_FORECAST, 0.0, 2.0 * (L - lv) * tens * Ed * esz + 2.0 * n * Ed * 4);
+      SPECA_TRY(launch_forecast_fold(ctx->geom, rt, h, h2, mod, mod_n, gate_off_dev, 2 * lv, 2 * L, D, st));
+    }
     // the verify block for real, on h
     SPECA_TRY(attn_branch(ctx, lv, h, n, nullptr));
     SPECA_TRY(mlp_branch(ctx, lv, h, n, nullptr, feat));
@@ -211,8 +242,11 @@ struct DiT final : Model {
     SPECA_TRY(ensure_partial(ctx, static_cast<size_t>(n) * verify_chunks(ctx->geom.E) * 3));
     std::memcpy(v.h_tau, tau_per_row, n * sizeof(float));
     SPECA_HIP(hipMemcpyAsync(v.tau_dev, v.h_tau, n * sizeof(float), hipMemcpyHostToDevice, st));
-    SPECA_TRY(launch_verify(ctx->cfg.metric, nullptr, ctx->geom.dtype, feat, SPECA_F32, ctx->geom.E, &ctx->geom, &rt, 2 * lv + 1, n,
-                            ctx->cfg.eps, v.tau_dev, v.partial, v.err_dev, v.acc_dev, st));
+    {
+      ProfScope ps(ctx, SPECA_PROF_VERIFY, 0.0, tens * Ed * esz + n * Ed * 4);
+      SPECA_TRY(launch_verify(ctx->cfg.metric, nullptr, ctx->geom.dtype, feat, SPECA_F32, ctx->geom.E, &ctx->geom, &rt, 2 * lv + 1, n,
+                              ctx->cfg.eps, v.tau_dev, v.partial, v.err_dev, v.acc_dev, st));
+    }
     SPECA_HIP(hipMemcpyAsync(v.h_err, v.err_dev, n * sizeof(float), hipMemcpyDeviceToHost, st));
     SPECA_HIP(hipMemcpyAsync(v.h_acc, v.acc_dev, n, hipMemcpyDeviceToHost, st));
     // finish every listed row from h2 while the verdict travels; rejected rows are overwritten by the fallback

@@ -1,11 +1,21 @@
 // Dispatch of the linear layers and attention to the kernel families (see gemm.h).
 #include "gemm.h"
 
+#include <cstdlib>
+
 namespace speca {
 
 Error launch_gemm_simple(int dtype, const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi,
                          hipStream_t st);
 Error launch_attention_simple(int dtype, const void* qkv, void* out, int rows, int T, int H, int hd, hipStream_t st);
+bool gemm_mfma_supported(const void* A, int64_t lda, const void* W, int64_t ldw, int N, int K);
+Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi, hipStream_t st);
+
+// SPECA_FORCE_SIMPLE=1 routes bf16 work to the plain-FMA kernels (A/B checks of the MFMA kernels).
+static bool force_simple() {
+  static const bool v = [] { const char* e = getenv("SPECA_FORCE_SIMPLE"); return e && e[0] == '1'; }();
+  return v;
+}
 
 Error launch_gemm(int dtype, const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi,
                   hipStream_t st) {
@@ -25,6 +35,8 @@ Error launch_gemm(int dtype, const void* A, int64_t lda, const void* W, int64_t 
   } else if (!epi.out || epi.ldo < N) {
     SPECA_FAIL(SPECA_EINVAL, "gemm: output missing");
   }
+  if (dtype == SPECA_BF16 && !force_simple() && gemm_mfma_supported(A, lda, W, ldw, N, K))
+    return launch_gemm_mfma(A, lda, W, ldw, M, N, K, epi, st);
   return launch_gemm_simple(dtype, A, lda, W, ldw, M, N, K, epi, st);
 }
 

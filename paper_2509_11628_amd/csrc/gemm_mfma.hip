@@ -1,0 +1,184 @@
+// bf16 MFMA GEMM for gfx950:  C[M,N] = A[M,K] * W[N,K]^T with fused epilogues.
+//
+// Tiling (wave64, v_mfma_f32_32x32x16_bf16):
+//   block tile BM x BN with 256 threads = 2 x 2 waves, wave tile (BM/2) x (BN/2);
+//   K is staged through LDS in steps of BK = 64 (double buffered, one barrier per step);
+//   global -> registers -> LDS with 16-byte accesses; LDS rows are padded by 16 bytes so that
+//   the 16-byte operand reads of 16 consecutive lanes fall into distinct banks.
+// Operand roles: the weight rows are the MFMA "A" operand and the token rows the "B" operand,
+// i.e. the instruction produces a tile of C^T.  A lane then owns, for one token, quads of
+// four consecutive output features, which is what the epilogues want (8-byte bf16 /
+// 16-byte fp32 accesses to C, the cache and the residual stream).
+// K is walked in order by every tile shape, so an output element is the same fp32 sequence
+// regardless of M, of the tile shape and of which rows share the launch.
+// Tiles are numbered so that the 8 XCDs (round-robin block dispatch) each work on a
+// contiguous range of tiles that share activations in their own L2.
+#include "epilogue.h"
+#include "gemm.h"
+
+namespace speca {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 64;
+constexpr int LDS_STRIDE = BK + 8;   // elements; 144-byte rows
+
+template <int BM, int BN, int MODE>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ W,
+                                                        int64_t ldw, int M, int N, int K, int tiles_m, int tiles_n, GemmEpi epi) {
+  constexpr int WM = BM / 2, WN = BN / 2;          // wave tile
+  constexpr int TM = WM / 32, TN = WN / 32;        // MFMA tiles per wave
+  constexpr int A_CHUNKS = BM * (BK / 8) / 256;    // 16-byte chunks per thread per stage
+  constexpr int W_CHUNKS = BN * (BK / 8) / 256;
+  extern __shared__ __align__(16) uint16_t smem[];
+  uint16_t* As = smem;                              // [2][BM][LDS_STRIDE]
+  uint16_t* Ws = smem + 2 * BM * LDS_STRIDE;        // [2][BN][LDS_STRIDE]
+
+  // XCD-aware tile id: blocks b, b+8, b+16, ... run on the same XCD; give them neighbouring tiles
+  // (the grid is rounded up to a multiple of 8; surplus blocks leave at once)
+  const int bid = blockIdx.x;
+  const int per_xcd = gridDim.x / 8;
+  const int tile = (bid % 8) * per_xcd + bid / 8;
+  if (tile >= tiles_m * tiles_n) return;
+  // tiles of one M-panel are consecutive: they share the activation panel
+  const int tm = tile / tiles_n, tn = tile - tm * tiles_n;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lhi = lane >> 5;
+
+  floatx16 acc[TN][TM];
+#pragma unroll
+  for (int i = 0; i < TN; ++i)
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;
+
+  uint4 ra[A_CHUNKS], rw[W_CHUNKS];
+  auto load_global = [&](int k0) {
+#pragma unroll
+    for (int c = 0; c < A_CHUNKS; ++c) {
+      const int id = tid + c * 256;
+      const int row = id >> 3, kc = (id & 7) * 8;
+      const int m = m0 + row, k = k0 + kc;
+      ra[c] = (m < M && k < K) ? *reinterpret_cast<const uint4*>(A + static_cast<int64_t>(m) * lda + k) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int c = 0; c < W_CHUNKS; ++c) {
+      const int id = tid + c * 256;
+      const int row = id >> 3, kc = (id & 7) * 8;
+      const int n = n0 + row, k = k0 + kc;
+      rw[c] = (n < N && k < K) ? *reinterpret_cast<const uint4*>(W + static_cast<int64_t>(n) * ldw + k) : make_uint4(0, 0, 0, 0);
+    }
+  };
+  auto store_lds = [&](int buf) {
+#pragma unroll
+    for (int c = 0; c < A_CHUNKS; ++c) {
+      const int id = tid + c * 256;
+      const int row = id >> 3, kc = (id & 7) * 8;
+      *reinterpret_cast<uint4*>(As + (buf * BM + row) * LDS_STRIDE + kc) = ra[c];
+    }
+#pragma unroll
+    for (int c = 0; c < W_CHUNKS; ++c) {
+      const int id = tid + c * 256;
+      const int row = id >> 3, kc = (id & 7) * 8;
+      *reinterpret_cast<uint4*>(Ws + (buf * BN + row) * LDS_STRIDE + kc) = rw[c];
+    }
+  };
+
+  const int nk = (K + BK - 1) / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) load_global((kt + 1) * BK);
+    const uint16_t* as = As + (buf * BM + wm * WM + l32) * LDS_STRIDE + lhi * 8;
+    const uint16_t* ws = Ws + (buf * BN + wn * WN + l32) * LDS_STRIDE + lhi * 8;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 fa[TM], fw[TN];
+#pragma unroll
+      for (int j = 0; j < TM; ++j) fa[j] = *reinterpret_cast<const bf16x8*>(as + j * 32 * LDS_STRIDE + ks * 16);
+#pragma unroll
+      for (int i = 0; i < TN; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(ws + i * 32 * LDS_STRIDE + ks * 16);
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue: acc[i][j][4*jj + ii] = C[m][n], m = m0 + wm*WM + j*32 + l32, n = n0 + wn*WN + i*32 + 8*jj + 4*lhi + ii
+#pragma unroll
+  for (int j = 0; j < TM; ++j) {
+    const int m = m0 + wm * WM + j * 32 + l32;
+    if (m >= M) continue;
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int n = n0 + wn * WN + i * 32 + 8 * jj + 4 * lhi;
+        if (n < N) {
+          float v[4] = {acc[i][j][4 * jj], acc[i][j][4 * jj + 1], acc[i][j][4 * jj + 2], acc[i][j][4 * jj + 3]};
+          epilogue_quad<bf16_t, MODE>(epi, m, n, v);
+        }
+      }
+  }
+}
+
+template <int BM, int BN>
+Error launch_tile(const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi, hipStream_t st) {
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  const int64_t nblk = static_cast<int64_t>(tiles_m) * tiles_n;
+  if (nblk > 0x7FFFFFFF) SPECA_FAIL(SPECA_EINVAL, "gemm: too many tiles");
+  const size_t smem = static_cast<size_t>(2) * (BM + BN) * LDS_STRIDE * sizeof(uint16_t);
+  const uint16_t* a = static_cast<const uint16_t*>(A);
+  const uint16_t* w = static_cast<const uint16_t*>(W);
+  dim3 grid(static_cast<unsigned>((nblk + 7) / 8 * 8));
+#define SPECA_LAUNCH(MODE_)                                                                                      \
+  {                                                                                                              \
+    auto kern = gemm_mfma_kernel<BM, BN, MODE_>;                                                                 \
+    static bool attr_set = false;   /* more than 64 KB of dynamic LDS must be requested once per kernel */         \
+    if (smem > 64 * 1024 && !attr_set) {                                                                         \
+      SPECA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem))); \
+      attr_set = true;                                                                                           \
+    }                                                                                                            \
+    kern<<<grid, 256, smem, st>>>(a, lda, w, ldw, M, N, K, tiles_m, tiles_n, epi);                               \
+  }
+  switch (epi.mode) {
+    case EPI_STORE: SPECA_LAUNCH(EPI_STORE) break;
+    case EPI_GELU: SPECA_LAUNCH(EPI_GELU) break;
+    case EPI_SILU: SPECA_LAUNCH(EPI_SILU) break;
+    case EPI_F32: SPECA_LAUNCH(EPI_F32) break;
+    case EPI_BRANCH: SPECA_LAUNCH(EPI_BRANCH) break;
+    default: SPECA_FAIL(SPECA_EINVAL, "gemm: epilogue mode %d", epi.mode);
+  }
+#undef SPECA_LAUNCH
+  SPECA_HIP(hipGetLastError());
+  return ok();
+}
+
+}  // namespace
+
+bool gemm_mfma_supported(const void* A, int64_t lda, const void* W, int64_t ldw, int N, int K) {
+  return (K % 8 == 0) && (lda % 8 == 0) && (ldw % 8 == 0) && (N % 8 == 0) && (reinterpret_cast<uintptr_t>(A) % 16 == 0) &&
+         (reinterpret_cast<uintptr_t>(W) % 16 == 0);
+}
+
+Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi, hipStream_t st) {
+  // 128x128 tiles; when that leaves the 256 CUs under-filled, 128x64 tiles double the tile count
+  const int64_t t128 = static_cast<int64_t>((M + 127) / 128) * ((N + 127) / 128);
+  if (t128 >= 512) return launch_tile<128, 128>(A, lda, W, ldw, M, N, K, epi, st);
+  return launch_tile<128, 64>(A, lda, W, ldw, M, N, K, epi, st);
+}
+
+}  // namespace speca

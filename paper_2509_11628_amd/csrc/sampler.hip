@@ -137,6 +137,7 @@ Error sample_impl(speca_ctx* ctx, float* latents, int batch, const speca_cond* c
         for (size_t i = 0; i < ns; ++i) rows.push_back(B + todo[i0 + i]);
       SPECA_TRY(ctx->model->full_step(ctx, latents, B, &c, labels.data(), s, rows.data(), static_cast<int>(rows.size()), model_out));
     }
+    ProfScope ps(ctx, SPECA_PROF_OTHER, 0.0, static_cast<double>(B) * n * 4 * (2 + R));
     SPECA_TRY(launch_solver_update(solver->kind, latents, model_out, B, n, guided ? solver->cfg_scale : 0.0f, solver->table[s],
                                    solver->table[s + 1], ctx->stream));
     if (trace) {

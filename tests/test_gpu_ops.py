@@ -1,0 +1,95 @@
+"""Parity of the dense contractions (linear layers, attention) with the oracle's
+plain definitions, through the C ABI (speca_linear, speca_attention).
+
+Tolerance: inputs are bf16-representable on both sides, products are exact in fp32,
+sums differ by fp32 rounding (<= K * 2^-24 relative to the sum of magnitudes), and the
+bf16 result is rounded once: the device value must lie within one bf16 step of the
+oracle's value rounded to bf16, plus that fp32 noise."""
+import numpy as np
+import pytest
+
+import speca_inputs as si
+from oracle import dit as odit, speca_core as core
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def _bd():
+    from paper_2509_11628_amd import binding as bd
+    return bd
+
+
+def _dev(a, dtype):
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    return torch.from_numpy(np.ascontiguousarray(a, np.float32)).cuda().to(td).contiguous()
+
+
+def _check(got, exp, dtype, K):
+    got = got.float().cpu().numpy().astype(np.float64)
+    scale = np.max(np.abs(exp))
+    if dtype == "f32":
+        assert np.max(np.abs(got - exp)) <= 1e-5 * scale
+    else:
+        expb = core.bf16_round(exp)
+        tol = np.abs(expb) * 2.0 ** -7 + K * 2.0 ** -22 * scale + 1e-30
+        bad = np.abs(got - expb) > tol
+        assert not bad.any(), (int(bad.sum()), float(np.max(np.abs(got - expb))))
+
+
+SHAPES = [  # M, N, K
+    (128, 128, 64), (256, 64, 128), (200, 192, 72), (1, 64, 64), (130, 1152, 1152), (515, 256, 4608), (16, 2304, 1152),
+    (300, 16, 64),
+]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("act", [0, 1, 2])
+def test_linear(M, N, K, dtype, act):
+    if act and (M, N, K) not in ((200, 192, 72), (130, 1152, 1152)):
+        pytest.skip("activations checked on two shapes")
+    bd = _bd()
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    a = si._store(rng.standard_normal((M, K)).astype(np.float32), dtype)
+    w = si._store((rng.standard_normal((N, K)) * 0.05).astype(np.float32), dtype)
+    b = si._store(rng.standard_normal(N).astype(np.float32) * 0.1, dtype)
+    out = bd.linear(_dev(a, dtype), _dev(w, dtype), _dev(b, dtype), act)
+    exp = odit.linear(a.astype(np.float64), w.astype(np.float64), b.astype(np.float64))
+    if act == 1:
+        exp = odit.gelu_tanh(exp)
+    if act == 2:
+        exp = odit.silu(exp)
+    _check(out, exp, dtype, K)
+
+
+def test_linear_row_result_independent_of_m():
+    bd = _bd()
+    rng = np.random.default_rng(0)
+    a = _dev(rng.standard_normal((700, 1152)), "bf16"); w = _dev(rng.standard_normal((1152, 1152)) * 0.03, "bf16")
+    full = bd.linear(a, w)
+    part = bd.linear(a[300:333].contiguous(), w)
+    assert torch.equal(full[300:333], part)         # bitwise: fixed K order, no split-K
+
+
+@pytest.mark.parametrize("rows,T,H,hd", [(2, 16, 4, 16), (1, 100, 2, 72), (2, 256, 3, 72), (1, 77, 2, 64), (1, 300, 2, 128), (1, 64, 1, 32)])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_attention(rows, T, H, hd, dtype):
+    bd = _bd()
+    rng = np.random.default_rng(T + hd)
+    qkv = si._store(rng.standard_normal((rows, T, 3, H, hd)).astype(np.float32), dtype)
+    out = bd.attention(_dev(qkv.reshape(rows, T, 3 * H * hd), dtype), H)
+    q, k, v = (qkv[:, :, i].transpose(0, 2, 1, 3).astype(np.float64) for i in range(3))
+    exp = odit.attention(q, k, v).transpose(0, 2, 1, 3).reshape(rows, T, H * hd)
+    got = out.float().cpu().numpy().astype(np.float64)
+    scale = np.max(np.abs(exp))
+    # bf16: probabilities and the output are rounded to bf16 on the device (2^-9 relative each)
+    assert np.max(np.abs(got - exp)) <= (2e-5 if dtype == "f32" else 1.2e-2) * scale
+
+
+def test_linear_rejects_bad_arguments():
+    bd = _bd()
+    a = torch.zeros((4, 8), device="cuda"); w = torch.zeros((6, 8), device="cuda")
+    with pytest.raises(bd.SpecaError) as e:
+        bd.linear(a, w)                              # N not a multiple of 4
+    assert e.value.code == bd.EINVAL
