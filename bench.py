@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpeCa sampling step on one MI355X.
+
+Workload (configuration 3): DiT-XL/2-shaped class-conditional model, bf16, 28 blocks,
+hidden 1152, 16 heads, 256 tokens, batch 8 with classifier-free guidance 1.5 (16 rows),
+DDIM, Taylor order 2, forced interval 5, thresholds tau0 = 0.1 decaying geometrically to
+0.02; seed-generated N(0, 0.02^2) weights and N(0,1) latents (synthetic).
+
+A "step" is one denoising step of the whole batch through speca_sample: schedule,
+speculative attempt (forecast + verify block + Eq. 4), fallback full step with cache
+refresh, solver update.  --steps K times exactly one K-step trajectory (default 50, the
+paper's setting), after one untimed W-step trajectory.  Inputs are resident in HBM before
+the timed region.
+
+Prints ONE JSON line.  `roofline` describes the dominant kernel class of the timed
+trajectory, measured with HIP events on the library's stream in a second, identical
+trajectory (event pairs around every launch would perturb the throughput figure);
+`cpu_baseline` times the NumPy oracle on a bounded sample of the same workload."""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0         # MI355X HBM3E
+
+
+def cpu_baseline(shape, weights, seconds_budget=30.0):
+    """The oracle as it stands, on the host cores: one full-compute step of one guided
+    sample (2 of the 16 rows), scaled to the 16-row batch step."""
+    from oracle import dit as odit
+    import speca_inputs as si
+    om = odit.DiTOracle(shape, weights)
+    x = si.make_latents(1, shape.in_channels, shape.latent_hw, 0)
+    xr = np.repeat(x, 2, axis=0)
+    t0 = time.time()
+    om.forward(xr, 980.0, [1, shape.num_classes])
+    dt = time.time() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": 1.0 / (8.0 * dt), "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"one full-compute step of one guided sample (2 of 16 rows, float64 NumPy) took {dt:.2f} s; "
+                      "scaled x8 to the 16-row batch step; speculative steps are not timed on the CPU"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tau0", type=float, default=0.1)
+    ap.add_argument("--tau-end", type=float, default=0.02)
+    ap.add_argument("--interval", type=int, default=5)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import speca_inputs as si
+    import paper_2509_11628_amd as sp
+    from paper_2509_11628_amd import binding as bd
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+
+    shape = si.dit_xl2("bf16")
+    B, cfg_scale, order = 8, 1.5, 2
+    weights = si.make_dit_weights(shape, 0)
+    ctx = sp.Context(sp.dit_desc(shape), sp.to_device(weights, bd.BF16))
+    ctx.init_cache(sp.make_cfg(order=order, interval=args.interval), 2 * B)
+    lat = si.make_latents(B, shape.in_channels, shape.latent_hw, 0)
+    lab = si.make_labels(B, shape.num_classes, 0)
+
+    def run(steps, tau=None, profile=False):
+        ts, ab = si.ddim_tables(steps)
+        if tau is None:
+            tau = bd.tau_geometric(args.tau0, args.tau_end / args.tau0, steps)
+        x = torch.from_numpy(lat).cuda()
+        torch.cuda.synchronize()
+        if profile:
+            ctx.profile_begin()
+        t0 = time.perf_counter()
+        tr = ctx.sample(x, ts, ab, tau, cfg_scale=cfg_scale, labels=lab)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        prof = ctx.profile_end() if profile else None
+        return dt, tr, prof
+
+    if args.warmup > 0:
+        run(args.warmup)
+    K = args.steps
+    dt, tr, _ = run(K)
+    _, _, prof = run(K, profile=True)
+    # the same trajectory without speculation (tau = 0: plain sampling) and with every attempt accepted
+    dt_plain, _, _ = run(K, tau=np.zeros(K, np.float32))
+    dt_acc, tr_acc, _ = run(K, tau=np.full(K, np.inf, np.float32))
+
+    dom = max(("gemm", "attention", "forecast", "verify", "other"), key=lambda k: prof[k]["ms"])
+    p = prof[dom]
+    if dom in ("gemm", "attention"):
+        ach = p["flops"] / (p["ms"] * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                "traffic": None}
+    else:
+        ach = p["bytes"] / (p["ms"] * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "traffic": None}
+    roof.update({"kernel": dom, "launches": p["launches"], "avg_launch_us": 1e3 * p["ms"] / max(p["launches"], 1),
+                 "flops_per_launch": p["flops"] / max(p["launches"], 1), "bytes_per_launch": p["bytes"] / max(p["launches"], 1)})
+
+    def cls(name, peak, key, scale):
+        q = prof[name]
+        if not q["launches"]:
+            return None
+        a = q[key] / (q["ms"] * 1e-3) / scale
+        return {"launches": q["launches"], "ms": q["ms"], "achieved": a, "frac": a / peak}
+
+    extras = {
+        "images_per_s": B * (K / dt) / K,
+        "accept_rate": tr["n_spec"] / float(B * K), "n_full": tr["n_full"], "n_spec": tr["n_spec"], "n_reject": tr["n_reject"],
+        "plain_sampling_steps_per_s": K / dt_plain,
+        "all_accepted_steps_per_s": K / dt_acc, "all_accepted_accept_rate": tr_acc["n_spec"] / float(B * K),
+        "gemm_mfma_TFLOPs": cls("gemm", PEAK_BF16_TFLOPS, "flops", 1e12),
+        "attention_mfma_TFLOPs": cls("attention", PEAK_BF16_TFLOPS, "flops", 1e12),
+        "forecast_hbm_GBps": cls("forecast", PEAK_HBM_GBPS, "bytes", 1e9),
+        "verify_hbm_GBps": cls("verify", PEAK_HBM_GBPS, "bytes", 1e9),
+        "other_ms": prof["other"]["ms"],
+    }
+    out = {
+        "metric": "denoising_steps_per_s", "value": K / dt, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": 1e3 * dt / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "config 3: DiT-XL/2-shaped bf16, batch 8 x CFG 1.5 (16 rows), 256 tokens, DDIM, Taylor order 2",
+                   "global_batch": B, "rows": 2 * B, "tokens": shape.tokens, "hidden": shape.hidden, "blocks": shape.depth,
+                   "order": order, "interval": args.interval, "tau0": args.tau0, "tau_end": args.tau_end, "parallelism": "single GPU"},
+        "roofline": roof,
+        "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(shape, weights),
+        "extras": extras,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

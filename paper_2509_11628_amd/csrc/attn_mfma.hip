@@ -1,0 +1,256 @@
+// bf16 MFMA attention for gfx950: softmax(q k^T / sqrt(hd)) v without mask, online softmax
+// in fp32 (no T x T matrix is ever written).
+//
+// One block = 128 queries of one (row, head): 4 waves x 32 queries.  Keys/values stream
+// through LDS in tiles of 64 keys, double buffered, one barrier per tile.
+// Both contractions run on v_mfma_f32_32x32x16_bf16 producing TRANSPOSED tiles:
+//   S^T[key][query] = K q^T   (A operand = key rows from LDS, B operand = the wave's query
+//                              rows, held in registers for the whole kernel)
+//   O^T[d][query]  += V^T P^T (A operand = V^T from LDS, B operand = P^T)
+// In both results a lane's 16 values belong to ONE query (column lane % 32), so the softmax
+// statistics and the rescaling of O are lane-local; only the max/sum over the lane pair
+// (lane, lane ^ 32) needs a shuffle.  The P^T operand is taken straight from the S^T
+// accumulators: the MFMA reduction index is a dummy, so the keys are simply fed to the second
+// MFMA in the order the first one left them in the lane (keys 16t+4h+0..3, 16t+8+4h+0..3 for
+// half-wave h), and V^T is read from LDS in that same order.
+// V is transposed on its way into LDS (8x8 register transposes, 16-byte LDS writes).
+// head_dim is padded with zeros to a multiple of 16 for q k^T and of 32 for P V.
+#include "gemm.h"
+
+namespace speca {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+union Frag {
+  uint4 u;
+  bf16x8 v;
+};
+
+__device__ inline uint32_t pack_bf16(float a, float b) {
+  return static_cast<uint32_t>(f32_to_bf16(a)) | (static_cast<uint32_t>(f32_to_bf16(b)) << 16);
+}
+
+template <int HD>
+__global__ __launch_bounds__(256) void attention_mfma_kernel(const uint16_t* __restrict__ qkv, uint16_t* __restrict__ out, int T,
+                                                             int H, float scale_log2e) {
+  constexpr int HD16 = (HD + 15) / 16 * 16, HD32 = (HD + 31) / 32 * 32;
+  constexpr int KS = HD16 / 16;         // reduction steps of q k^T
+  constexpr int DT = HD32 / 32;         // 32-row tiles of O^T
+  constexpr int KST = HD16 + 8;         // LDS row stride of the key tile (elements)
+  constexpr int VST = 64 + 8;           // LDS row stride of the transposed value tile
+  constexpr int CH = HD / 8;            // 16-byte chunks per key/value row
+  constexpr int K_CHUNKS = (64 * CH + 255) / 256;
+  static_assert(HD % 8 == 0, "head_dim must be a multiple of 8");
+  extern __shared__ __align__(16) uint16_t smem[];
+  uint16_t* Ks = smem;                        // [2][64][KST]
+  uint16_t* Vt = smem + 2 * 64 * KST;         // [2][HD32][VST]
+
+  const int row = blockIdx.z, head = blockIdx.y, q0 = blockIdx.x * 128;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int64_t D = static_cast<int64_t>(H) * HD;
+  const uint16_t* base = qkv + static_cast<int64_t>(row) * T * 3 * D + head * HD;
+
+  // zero padding of both buffers: key columns [HD, HD16) and value rows [HD, HD32); never overwritten
+  if (HD16 > HD)
+    for (int i = tid; i < 2 * 64 * (HD16 - HD); i += 256) Ks[(i / (HD16 - HD)) * KST + HD + i % (HD16 - HD)] = 0;
+  if (HD32 > HD)
+    for (int i = tid; i < 2 * (HD32 - HD) * 64; i += 256) {
+      const int b = i / ((HD32 - HD) * 64), r = (i / 64) % (HD32 - HD), c = i % 64;
+      Vt[(b * HD32 + HD + r) * VST + c] = 0;
+    }
+
+  // the wave's 32 queries as B operand, resident in registers
+  Frag qf[KS];
+  {
+    const int q = q0 + wave * 32 + l32;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int d = ks * 16 + lhi * 8;
+      qf[ks].u = (q < T && d < HD) ? *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(q) * 3 * D + d) : make_uint4(0, 0, 0, 0);
+    }
+  }
+
+  floatx16 o[DT];
+#pragma unroll
+  for (int i = 0; i < DT; ++i)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) o[i][q] = 0.0f;
+  float mrun = -INFINITY, lrun = 0.0f;     // running max (of scaled scores, log2 domain) and this lane's partial sum
+
+  uint4 rk[K_CHUNKS], rv[8];
+  const bool v_thread = tid < 8 * CH;
+  const int v_kb = tid / CH, v_dc = tid % CH;   // 8x8 block: keys v_kb*8.., dims v_dc*8..
+  auto load_global = [&](int k0) {
+#pragma unroll
+    for (int c = 0; c < K_CHUNKS; ++c) {
+      const int id = tid + c * 256;
+      const int key = id / CH, dc = id - key * CH;
+      rk[c] = (id < 64 * CH && k0 + key < T) ? *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(k0 + key) * 3 * D + D + dc * 8)
+                                             : make_uint4(0, 0, 0, 0);
+    }
+    if (v_thread) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int key = k0 + v_kb * 8 + i;
+        rv[i] = key < T ? *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(key) * 3 * D + 2 * D + v_dc * 8) : make_uint4(0, 0, 0, 0);
+      }
+    }
+  };
+  auto store_lds = [&](int buf) {
+#pragma unroll
+    for (int c = 0; c < K_CHUNKS; ++c) {
+      const int id = tid + c * 256;
+      const int key = id / CH, dc = id - key * CH;
+      if (id < 64 * CH) *reinterpret_cast<uint4*>(Ks + (buf * 64 + key) * KST + dc * 8) = rk[c];
+    }
+    if (v_thread) {
+      // rv[i] = 8 dims of key i  ->  8 rows (dims) of 8 keys
+      const uint32_t w[8][4] = {{rv[0].x, rv[0].y, rv[0].z, rv[0].w}, {rv[1].x, rv[1].y, rv[1].z, rv[1].w},
+                                {rv[2].x, rv[2].y, rv[2].z, rv[2].w}, {rv[3].x, rv[3].y, rv[3].z, rv[3].w},
+                                {rv[4].x, rv[4].y, rv[4].z, rv[4].w}, {rv[5].x, rv[5].y, rv[5].z, rv[5].w},
+                                {rv[6].x, rv[6].y, rv[6].z, rv[6].w}, {rv[7].x, rv[7].y, rv[7].z, rv[7].w}};
+#pragma unroll
+      for (int dd = 0; dd < 8; ++dd) {
+        uint32_t r[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const uint32_t a = w[2 * kk][dd >> 1], b = w[2 * kk + 1][dd >> 1];
+          r[kk] = (dd & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
+        }
+        *reinterpret_cast<uint4*>(Vt + (buf * HD32 + v_dc * 8 + dd) * VST + v_kb * 8) = make_uint4(r[0], r[1], r[2], r[3]);
+      }
+    }
+  };
+
+  const int ntiles = (T + 63) / 64;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int kt = 0; kt < ntiles; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < ntiles) load_global((kt + 1) * 64);
+
+    // S^T for the two 32-key sub-tiles
+    floatx16 s[2];
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) s[st][q] = 0.0f;
+      const uint16_t* kp = Ks + (buf * 64 + st * 32 + l32) * KST + lhi * 8;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        Frag kf;
+        kf.u = *reinterpret_cast<const uint4*>(kp + ks * 16);
+        s[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, s[st], 0, 0, 0);
+      }
+    }
+    // scale to the log2 domain, mask the ragged tail, row max over the lane pair
+    float tmax = -INFINITY;
+    const int kbase = kt * 64;
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int key = kbase + st * 32 + 8 * (q >> 2) + 4 * lhi + (q & 3);
+        const float v = key < T ? s[st][q] * scale_log2e : -INFINITY;
+        s[st][q] = v;
+        tmax = fmaxf(tmax, v);
+      }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float mnew = fmaxf(mrun, tmax);
+    const float corr = exp2f(mrun - mnew);
+    mrun = mnew;
+    float psum = 0.0f;
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const float p = exp2f(s[st][q] - mnew);
+        s[st][q] = p;
+        psum += p;
+      }
+    lrun = lrun * corr + psum;
+#pragma unroll
+    for (int i = 0; i < DT; ++i)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) o[i][q] *= corr;
+
+    // O^T += V^T P^T, four reduction steps of 16 keys
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int st = t >> 1, j0 = (t & 1) * 8;      // accumulator entries j0 .. j0+7 of sub-tile st
+      Frag pf;
+      pf.u = make_uint4(pack_bf16(s[st][j0], s[st][j0 + 1]), pack_bf16(s[st][j0 + 2], s[st][j0 + 3]),
+                        pack_bf16(s[st][j0 + 4], s[st][j0 + 5]), pack_bf16(s[st][j0 + 6], s[st][j0 + 7]));
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        const uint16_t* vp = Vt + (buf * HD32 + dt * 32 + l32) * VST + t * 16 + 4 * lhi;
+        const uint2 lo = *reinterpret_cast<const uint2*>(vp);
+        const uint2 hi = *reinterpret_cast<const uint2*>(vp + 8);
+        Frag vf;
+        vf.u = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[dt], 0, 0, 0);
+      }
+    }
+    if (kt + 1 < ntiles) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  const float ltot = lrun + __shfl_xor(lrun, 32, 64);
+  const float inv = 1.0f / ltot;
+  const int q = q0 + wave * 32 + l32;
+  if (q < T) {
+    uint16_t* op = out + (static_cast<int64_t>(row) * T + q) * D + head * HD;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int d = dt * 32 + 8 * jj + 4 * lhi;
+        if (d < HD) {
+          uint2 r;
+          r.x = pack_bf16(o[dt][4 * jj] * inv, o[dt][4 * jj + 1] * inv);
+          r.y = pack_bf16(o[dt][4 * jj + 2] * inv, o[dt][4 * jj + 3] * inv);
+          *reinterpret_cast<uint2*>(op + d) = r;
+        }
+      }
+  }
+}
+
+template <int HD>
+Error launch_hd(const void* qkv, void* out, int rows, int T, int H, hipStream_t st) {
+  constexpr int HD16 = (HD + 15) / 16 * 16, HD32 = (HD + 31) / 32 * 32;
+  const size_t smem = static_cast<size_t>(2) * (64 * (HD16 + 8) + HD32 * (64 + 8)) * sizeof(uint16_t);
+  auto kern = attention_mfma_kernel<HD>;
+  static bool attr_set = false;
+  if (smem > 64 * 1024 && !attr_set) {
+    SPECA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem)));
+    attr_set = true;
+  }
+  dim3 grid((T + 127) / 128, H, rows);
+  const float scale_log2e = 1.4426950408889634f / sqrtf(static_cast<float>(HD));
+  kern<<<grid, 256, smem, st>>>(static_cast<const uint16_t*>(qkv), static_cast<uint16_t*>(out), T, H, scale_log2e);
+  SPECA_HIP(hipGetLastError());
+  return ok();
+}
+
+}  // namespace
+
+bool attention_mfma_supported(const void* qkv, const void* out, int H, int hd) {
+  return (hd == 64 || hd == 72 || hd == 128) && reinterpret_cast<uintptr_t>(qkv) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 8 == 0;
+}
+
+Error launch_attention_mfma(const void* qkv, void* out, int rows, int T, int H, int hd, hipStream_t st) {
+  if (rows > 65535 || H > 65535) SPECA_FAIL(SPECA_EINVAL, "attention: grid too large");
+  switch (hd) {
+    case 64: return launch_hd<64>(qkv, out, rows, T, H, st);
+    case 72: return launch_hd<72>(qkv, out, rows, T, H, st);
+    case 128: return launch_hd<128>(qkv, out, rows, T, H, st);
+  }
+  SPECA_FAIL(SPECA_EUNSUPPORTED, "attention: head_dim %d has no MFMA kernel", hd);
+}
+
+}  // namespace speca

@@ -11,6 +11,9 @@ Error launch_attention_simple(int dtype, const void* qkv, void* out, int rows, i
 bool gemm_mfma_supported(const void* A, int64_t lda, const void* W, int64_t ldw, int N, int K);
 Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi, hipStream_t st);
 
+bool attention_mfma_supported(const void* qkv, const void* out, int H, int hd);
+Error launch_attention_mfma(const void* qkv, void* out, int rows, int T, int H, int hd, hipStream_t st);
+
 // SPECA_FORCE_SIMPLE=1 routes bf16 work to the plain-FMA kernels (A/B checks of the MFMA kernels).
 static bool force_simple() {
   static const bool v = [] { const char* e = getenv("SPECA_FORCE_SIMPLE"); return e && e[0] == '1'; }();
@@ -42,6 +45,8 @@ Error launch_gemm(int dtype, const void* A, int64_t lda, const void* W, int64_t 
 
 Error launch_attention(int dtype, const void* qkv, void* out, int rows, int T, int H, int hd, hipStream_t st) {
   if (!qkv || !out || rows < 1 || T < 1 || H < 1) SPECA_FAIL(SPECA_EINVAL, "attention: bad arguments");
+  if (dtype == SPECA_BF16 && !force_simple() && attention_mfma_supported(qkv, out, H, hd))
+    return launch_attention_mfma(qkv, out, rows, T, H, hd, st);
   return launch_attention_simple(dtype, qkv, out, rows, T, H, hd, st);
 }
 
