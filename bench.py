@@ -54,8 +54,103 @@ def cpu_baseline(shape, weights, seconds_budget=30.0):
                       "scaled x8 to the 16-row batch step; speculative steps are not timed on the CPU"}
 
 
+def bench_forecast(args):
+    """Configuration 2: the HBM-bound kernels in isolation.  Cache of 28 slots x 8 rows x 256
+    tokens x 1152 hidden in bf16, order 2, built from 3 reference steps (0, 4, 8) of a seeded
+    quadratic-in-step trajectory plus noise; a step = materialised forecast of every slot at
+    k = 1 + Eq. 4 verification of the last slot against a seeded perturbed target."""
+    import torch
+    import speca_inputs as si
+    import paper_2509_11628_amd as sp
+    from paper_2509_11628_amd import binding as bd
+    slots, B, T, D, m = 28, 8, 256, 1152, 2
+    ctx = sp.Context(sp.cache_only_desc(slots, T, D, bd.BF16))
+    ctx.init_cache(sp.make_cfg(order=m, interval=4), B)
+    rows = list(range(B))
+    for s_, f in zip([0, 4, 8], si.feature_trajectory(slots, B, T, D, [0, 4, 8], seed=0, dtype="bf16")):
+        ctx.refresh(s_, rows, torch.from_numpy(f).cuda().bfloat16())
+    out = torch.empty((slots, B, T, D), dtype=torch.bfloat16, device="cuda")
+    ctx.forecast(9, rows, out)
+    pred = out[slots - 1].float().cpu().numpy()
+    truth = torch.from_numpy(si.perturbed_target(pred, si.VERIFY_DELTAS, seed=0, dtype="bf16")).cuda().bfloat16()
+    last = out[slots - 1]
+
+    def step():
+        ctx.forecast(9, rows, out)
+        return ctx.verify(last, truth, tau=0.05)
+
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        err, acc = step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ctx.profile_begin()
+    for _ in range(args.steps):
+        step()
+    prof = ctx.profile_end()
+    p = prof["forecast"]
+    ach = p["bytes"] / (p["ms"] * 1e-3) / 1e9
+    v = prof["verify"]
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import speca_core as core
+        feats = si.feature_trajectory(1, 1, T, D, [0, 4, 8], seed=0, dtype="bf16")
+        c = core.FeatureCache(1, m, "taylor", "bf16")
+        for s_, f in zip([0, 4, 8], feats):
+            c.refresh(s_, [f[0, 0]])
+        t1 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t1 < 10.0:
+            core.bf16_round(c.forecast(9, 0)); n += 1
+        dtc = (time.perf_counter() - t1) / n
+        cpu = {"value": 1.0 / (dtc * slots * B), "unit": "steps/s", "cores": 1, "kind": "oracle",
+               "sample": f"forecast of one (slot,row) tensor of {T * D} elements took {dtc * 1e3:.2f} ms (float64 NumPy, single thread); "
+                         f"scaled x{slots * B} to all slots and rows"}
+    out_json = {
+        "metric": "forecast_verify_steps_per_s", "value": args.steps / dt, "unit": "steps/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config 2: forecast + verify in isolation, 28 slots x 8 rows x 256 tokens x 1152 hidden, bf16, order 2",
+                   "slots": slots, "rows": B, "tokens": T, "hidden": D, "order": m},
+        "roofline": {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "traffic": None,
+                     "kernel": "forecast", "launches": p["launches"], "avg_launch_us": 1e3 * p["ms"] / p["launches"],
+                     "bytes_per_launch": p["bytes"] / p["launches"]},
+        "cpu_baseline": cpu,
+        "extras": {"accepted": [bool(a) for a in acc], "errors": [float(e) for e in err],
+                   "verify_avg_launch_us": 1e3 * v["ms"] / max(v["launches"], 1), "verify_bytes_per_launch": v["bytes"] / max(v["launches"], 1)},
+    }
+    print(json.dumps(out_json))
+
+
+def bench_copy(args):
+    """A plain device copy of known size (512 MiB read + 512 MiB written per step): the
+    calibration run for the FETCH_SIZE / WRITE_SIZE counters and a measured HBM ceiling."""
+    import torch
+    n = 512 * 1024 * 1024 // 2
+    a = torch.empty(n, dtype=torch.bfloat16, device="cuda").normal_()
+    b = torch.empty_like(a)
+    for _ in range(max(args.warmup, 1)):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    gbps = 2 * n * 2 / dt / 1e9
+    print(json.dumps({"metric": "copy_GBps", "value": gbps, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                      "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+                      "data": "synthetic", "config": {"workload": "plain copy, 512 MiB in + 512 MiB out"},
+                      "roofline": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": gbps / PEAK_HBM_GBPS, "traffic": 2.0 * n * 2},
+                      "cpu_baseline": None}))
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", choices=["dit_xl2", "forecast", "copy"], default="dit_xl2")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=50)
@@ -76,6 +171,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
+    if args.workload == "forecast":
+        return bench_forecast(args)
+    if args.workload == "copy":
+        return bench_copy(args)
 
     shape = si.dit_xl2("bf16")
     B, cfg_scale, order = 8, 1.5, 2
