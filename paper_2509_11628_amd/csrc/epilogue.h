@@ -7,9 +7,12 @@
 
 namespace speca {
 
+// GELU, tanh form, with tanh(u) = 1 - 2 / (1 + exp(2u)) (exact identity; saturates correctly at both ends)
 __device__ inline float gelu_tanh_f(float a) {
   const float k = 0.7978845608028654f;   // sqrt(2/pi)
-  return 0.5f * a * (1.0f + tanhf(k * (a + 0.044715f * a * a * a)));
+  const float u = k * (a + 0.044715f * a * a * a);
+  const float t = 1.0f - __fdividef(2.0f, 1.0f + __expf(2.0f * u));
+  return 0.5f * a * (1.0f + t);
 }
 __device__ inline float silu_f(float a) { return a / (1.0f + __expf(-a)); }
 

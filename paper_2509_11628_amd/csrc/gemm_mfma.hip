@@ -8,7 +8,8 @@
 // Operand roles: the weight rows are the MFMA "A" operand and the token rows the "B" operand,
 // i.e. the instruction produces a tile of C^T.  A lane then owns, for one token, quads of
 // four consecutive output features, which is what the epilogues want (8-byte bf16 /
-// 16-byte fp32 accesses to C, the cache and the residual stream).
+// 16-byte fp32 accesses to C, the cache and the residual stream); the tile is re-laid through
+// LDS before the epilogue so those accesses are also contiguous across lanes.
 // K is walked in order by every tile shape, so an output element is the same fp32 sequence
 // regardless of M, of the tile shape and of which rows share the launch.
 // Tiles are numbered so that the 8 XCDs (round-robin block dispatch) each work on a
@@ -117,21 +118,34 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
     __syncthreads();
   }
 
-  // epilogue: acc[i][j][4*jj + ii] = C[m][n], m = m0 + wm*WM + j*32 + l32, n = n0 + wn*WN + i*32 + 8*jj + 4*lhi + ii
+  // epilogue.  acc[i][j][4*jj + ii] = C[m][n] with m = wm*WM + j*32 + l32, n = wn*WN + i*32 + 8*jj + 4*lhi + ii
+  // inside the tile.  The tile goes through LDS once (fp32, rows padded by 16 bytes: conflict-free for
+  // the 16-byte writes of 16 consecutive lanes) so that every global access of the epilogue is a
+  // contiguous run along n: a half-wave covers one 512-byte (fp32) / 256-byte (bf16) row segment.
+  constexpr int CST = BN + 4;                        // floats per staged row
+  float* Cs = reinterpret_cast<float*>(smem);        // [BM][CST]; the operand buffers are dead by now
 #pragma unroll
-  for (int j = 0; j < TM; ++j) {
-    const int m = m0 + wm * WM + j * 32 + l32;
-    if (m >= M) continue;
+  for (int j = 0; j < TM; ++j)
 #pragma unroll
     for (int i = 0; i < TN; ++i)
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
-        const int n = n0 + wn * WN + i * 32 + 8 * jj + 4 * lhi;
-        if (n < N) {
-          float v[4] = {acc[i][j][4 * jj], acc[i][j][4 * jj + 1], acc[i][j][4 * jj + 2], acc[i][j][4 * jj + 3]};
-          epilogue_quad<bf16_t, MODE>(epi, m, n, v);
-        }
+        const int r = wm * WM + j * 32 + l32, c = wn * WN + i * 32 + 8 * jj + 4 * lhi;
+        *reinterpret_cast<float4*>(Cs + r * CST + c) =
+            make_float4(acc[i][j][4 * jj], acc[i][j][4 * jj + 1], acc[i][j][4 * jj + 2], acc[i][j][4 * jj + 3]);
       }
+  __syncthreads();
+  constexpr int QPR = BN / 4;                        // quads per row
+  constexpr int RPP = 256 / QPR;                     // rows per pass
+  const int qc = (tid % QPR) * 4, qr = tid / QPR;
+#pragma unroll 4
+  for (int r = qr; r < BM; r += RPP) {
+    const int m = m0 + r, n = n0 + qc;
+    if (m < M && n < N) {
+      const float4 t = *reinterpret_cast<const float4*>(Cs + r * CST + qc);
+      float v[4] = {t.x, t.y, t.z, t.w};
+      epilogue_quad<bf16_t, MODE>(epi, m, n, v);
+    }
   }
 }
 
@@ -140,7 +154,9 @@ Error launch_tile(const void* A, int64_t lda, const void* W, int64_t ldw, int M,
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const int64_t nblk = static_cast<int64_t>(tiles_m) * tiles_n;
   if (nblk > 0x7FFFFFFF) SPECA_FAIL(SPECA_EINVAL, "gemm: too many tiles");
-  const size_t smem = static_cast<size_t>(2) * (BM + BN) * LDS_STRIDE * sizeof(uint16_t);
+  const size_t smem_ops = static_cast<size_t>(2) * (BM + BN) * LDS_STRIDE * sizeof(uint16_t);
+  const size_t smem_epi = static_cast<size_t>(BM) * (BN + 4) * sizeof(float);
+  const size_t smem = smem_ops > smem_epi ? smem_ops : smem_epi;
   const uint16_t* a = static_cast<const uint16_t*>(A);
   const uint16_t* w = static_cast<const uint16_t*>(W);
   dim3 grid(static_cast<unsigned>((nblk + 7) / 8 * 8));
@@ -175,9 +191,10 @@ bool gemm_mfma_supported(const void* A, int64_t lda, const void* W, int64_t ldw,
 }
 
 Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi, hipStream_t st) {
-  // 128x128 tiles; when that leaves the 256 CUs under-filled, 128x64 tiles double the tile count
+  // 128x128 tiles (measured faster than 128x64 even at 288 tiles: half the operand traffic per
+  // FLOP); 128x64 only for problems too small to give each CU a tile otherwise
   const int64_t t128 = static_cast<int64_t>((M + 127) / 128) * ((N + 127) / 128);
-  if (t128 >= 512) return launch_tile<128, 128>(A, lda, W, ldw, M, N, K, epi, st);
+  if (t128 >= 200) return launch_tile<128, 128>(A, lda, W, ldw, M, N, K, epi, st);
   return launch_tile<128, 64>(A, lda, W, ldw, M, N, K, epi, st);
 }
 
