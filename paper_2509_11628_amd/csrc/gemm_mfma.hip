@@ -1,8 +1,9 @@
 // bf16 MFMA GEMM for gfx950:  C[M,N] = A[M,K] * W[N,K]^T with fused epilogues.
 //
 // Tiling (wave64, v_mfma_f32_32x32x16_bf16):
-//   block tile BM x BN with 256 threads = 2 x 2 waves, wave tile (BM/2) x (BN/2);
-//   K is staged through LDS in steps of BK = 64 (double buffered, one barrier per step);
+//   block tile BM x BN with WGM x WGN waves, wave tile (BM/WGM) x (BN/WGN);
+//   K is staged through LDS in steps of BK = 64 (double buffered, one barrier per step), with two
+//   further K-tiles in flight in registers (prefetch distance 2);
 //   global -> registers -> LDS with 16-byte accesses; LDS rows are padded by 16 bytes so that
 //   the 16-byte operand reads of 16 consecutive lanes fall into distinct banks.
 // Operand roles: the weight rows are the MFMA "A" operand and the token rows the "B" operand,
@@ -27,30 +28,47 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int BK = 64;
 constexpr int LDS_STRIDE = BK + 8;   // elements; 144-byte rows
 
-template <int BM, int BN, int MODE>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ W,
-                                                        int64_t ldw, int M, int N, int K, int tiles_m, int tiles_n, GemmEpi epi) {
-  constexpr int WM = BM / 2, WN = BN / 2;          // wave tile
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // first-class vector: stays in registers
+
+// KTAIL: K is not a multiple of BK; the last operand tile is zero-filled by predicated loads.
+template <int BM, int BN, int WGM, int WGN, int MODE, bool KTAIL>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const uint16_t* __restrict__ A, int64_t lda,
+                                                                   const uint16_t* __restrict__ W, int64_t ldw, int M, int N, int K,
+                                                                   int tiles_m, int tiles_n, int group_m, GemmEpi epi) {
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int WM = BM / WGM, WN = BN / WGN;      // wave tile
   constexpr int TM = WM / 32, TN = WN / 32;        // MFMA tiles per wave
-  constexpr int A_CHUNKS = BM * (BK / 8) / 256;    // 16-byte chunks per thread per stage
-  constexpr int W_CHUNKS = BN * (BK / 8) / 256;
+  constexpr int A_CHUNKS = BM * (BK / 8) / NT;     // 16-byte chunks per thread per stage
+  constexpr int W_CHUNKS = BN * (BK / 8) / NT;
+  static_assert(BM * (BK / 8) % NT == 0 && BN * (BK / 8) % NT == 0, "tile does not divide among the threads");
   extern __shared__ __align__(16) uint16_t smem[];
   uint16_t* As = smem;                              // [2][BM][LDS_STRIDE]
   uint16_t* Ws = smem + 2 * BM * LDS_STRIDE;        // [2][BN][LDS_STRIDE]
 
   // XCD-aware tile id: blocks b, b+8, b+16, ... run on the same XCD; give them neighbouring tiles
-  // (the grid is rounded up to a multiple of 8; surplus blocks leave at once)
+  // (the grid is rounded up to a multiple of 8; surplus blocks leave at once).  Inside an XCD's
+  // range tiles are walked in groups of group_m M-panels, N fastest across the group's panels,
+  // so that the tiles in flight at one time form a compact rectangle and share operand panels
+  // in that XCD's L2.
   const int bid = blockIdx.x;
   const int per_xcd = gridDim.x / 8;
   const int tile = (bid % 8) * per_xcd + bid / 8;
   if (tile >= tiles_m * tiles_n) return;
-  // tiles of one M-panel are consecutive: they share the activation panel
-  const int tm = tile / tiles_n, tn = tile - tm * tiles_n;
+  int tm, tn;
+  {
+    const int per_group = group_m * tiles_n;
+    const int g = tile / per_group;
+    const int first = g * group_m;
+    const int h = tiles_m - first < group_m ? tiles_m - first : group_m;
+    const int r = tile - g * per_group;
+    tm = first + r % h;
+    tn = r / h;
+  }
   const int m0 = tm * BM, n0 = tn * BN;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
   const int l32 = lane & 31, lhi = lane >> 5;
 
   floatx16 acc[TN][TM];
@@ -61,62 +79,87 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;
 
-  uint4 ra[A_CHUNKS], rw[W_CHUNKS];
-  auto load_global = [&](int k0) {
-#pragma unroll
-    for (int c = 0; c < A_CHUNKS; ++c) {
-      const int id = tid + c * 256;
-      const int row = id >> 3, kc = (id & 7) * 8;
-      const int m = m0 + row, k = k0 + kc;
-      ra[c] = (m < M && k < K) ? *reinterpret_cast<const uint4*>(A + static_cast<int64_t>(m) * lda + k) : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int c = 0; c < W_CHUNKS; ++c) {
-      const int id = tid + c * 256;
-      const int row = id >> 3, kc = (id & 7) * 8;
-      const int n = n0 + row, k = k0 + kc;
-      rw[c] = (n < N && k < K) ? *reinterpret_cast<const uint4*>(W + static_cast<int64_t>(n) * ldw + k) : make_uint4(0, 0, 0, 0);
-    }
-  };
-  auto store_lds = [&](int buf) {
-#pragma unroll
-    for (int c = 0; c < A_CHUNKS; ++c) {
-      const int id = tid + c * 256;
-      const int row = id >> 3, kc = (id & 7) * 8;
-      *reinterpret_cast<uint4*>(As + (buf * BM + row) * LDS_STRIDE + kc) = ra[c];
-    }
-#pragma unroll
-    for (int c = 0; c < W_CHUNKS; ++c) {
-      const int id = tid + c * 256;
-      const int row = id >> 3, kc = (id & 7) * 8;
-      *reinterpret_cast<uint4*>(Ws + (buf * BN + row) * LDS_STRIDE + kc) = rw[c];
-    }
-  };
-
+  // Operand staging: two register sets, i.e. two K-tiles in flight per block (prefetch distance 2)
+  // on top of the LDS double buffer.  Loads are branch-free: rows beyond M / N are clamped to the
+  // last row (their results are never stored) and tiles beyond K re-read the last tile, so the
+  // compiler can count outstanding loads exactly instead of draining them at every branch.
   const int nk = (K + BK - 1) / BK;
-  load_global(0);
-  store_lds(0);
+  const uint16_t* pa[A_CHUNKS];
+  const uint16_t* pw[W_CHUNKS];
+  int kca[A_CHUNKS], kcw[W_CHUNKS];
+#pragma unroll
+  for (int c = 0; c < A_CHUNKS; ++c) {
+    const int id = tid + c * NT;
+    const int row = id >> 3;
+    kca[c] = (id & 7) * 8;
+    const int m = m0 + row < M ? m0 + row : M - 1;
+    pa[c] = A + static_cast<int64_t>(m) * lda + kca[c];
+  }
+#pragma unroll
+  for (int c = 0; c < W_CHUNKS; ++c) {
+    const int id = tid + c * NT;
+    const int row = id >> 3;
+    kcw[c] = (id & 7) * 8;
+    const int n = n0 + row < N ? n0 + row : N - 1;
+    pw[c] = W + static_cast<int64_t>(n) * ldw + kcw[c];
+  }
+  u32x4 ra0[A_CHUNKS], rw0[W_CHUNKS], ra1[A_CHUNKS], rw1[W_CHUNKS];
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+#define SPECA_LOADG(ra, rw, kt_)                                                                               \
+  {                                                                                                            \
+    const int k0_ = ((kt_) < nk ? (kt_) : nk - 1) * BK;                                                        \
+    _Pragma("unroll") for (int c = 0; c < A_CHUNKS; ++c) {                                                     \
+      if (KTAIL) ra[c] = (k0_ + kca[c] < K) ? *reinterpret_cast<const u32x4*>(pa[c] + k0_) : zero4;            \
+      else ra[c] = *reinterpret_cast<const u32x4*>(pa[c] + k0_);                                               \
+    }                                                                                                          \
+    _Pragma("unroll") for (int c = 0; c < W_CHUNKS; ++c) {                                                     \
+      if (KTAIL) rw[c] = (k0_ + kcw[c] < K) ? *reinterpret_cast<const u32x4*>(pw[c] + k0_) : zero4;            \
+      else rw[c] = *reinterpret_cast<const u32x4*>(pw[c] + k0_);                                               \
+    }                                                                                                          \
+  }
+#define SPECA_STOREL(ra, rw, buf)                                                                              \
+  {                                                                                                            \
+    _Pragma("unroll") for (int c = 0; c < A_CHUNKS; ++c) {                                                     \
+      const int id = tid + c * NT;                                                                             \
+      *reinterpret_cast<u32x4*>(As + ((buf) * BM + (id >> 3)) * LDS_STRIDE + (id & 7) * 8) = ra[c];            \
+    }                                                                                                          \
+    _Pragma("unroll") for (int c = 0; c < W_CHUNKS; ++c) {                                                     \
+      const int id = tid + c * NT;                                                                             \
+      *reinterpret_cast<u32x4*>(Ws + ((buf) * BN + (id >> 3)) * LDS_STRIDE + (id & 7) * 8) = rw[c];            \
+    }                                                                                                          \
+  }
+#define SPECA_COMPUTE(buf)                                                                                     \
+  {                                                                                                            \
+    const uint16_t* as = As + ((buf) * BM + wm * WM + l32) * LDS_STRIDE + lhi * 8;                             \
+    const uint16_t* ws = Ws + ((buf) * BN + wn * WN + l32) * LDS_STRIDE + lhi * 8;                             \
+    _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                                   \
+      bf16x8 fa[TM], fw[TN];                                                                                   \
+      _Pragma("unroll") for (int j = 0; j < TM; ++j) fa[j] = *reinterpret_cast<const bf16x8*>(as + j * 32 * LDS_STRIDE + ks * 16); \
+      _Pragma("unroll") for (int i = 0; i < TN; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(ws + i * 32 * LDS_STRIDE + ks * 16); \
+      _Pragma("unroll") for (int i = 0; i < TN; ++i) _Pragma("unroll") for (int j = 0; j < TM; ++j)            \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);                  \
+    }                                                                                                          \
+  }
+
+  SPECA_LOADG(ra0, rw0, 0);
+  SPECA_LOADG(ra1, rw1, 1);
+  SPECA_STOREL(ra0, rw0, 0);
+  SPECA_LOADG(ra0, rw0, 2);
   __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) load_global((kt + 1) * BK);
-    const uint16_t* as = As + (buf * BM + wm * WM + l32) * LDS_STRIDE + lhi * 8;
-    const uint16_t* ws = Ws + (buf * BN + wn * WN + l32) * LDS_STRIDE + lhi * 8;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[TM], fw[TN];
-#pragma unroll
-      for (int j = 0; j < TM; ++j) fa[j] = *reinterpret_cast<const bf16x8*>(as + j * 32 * LDS_STRIDE + ks * 16);
-#pragma unroll
-      for (int i = 0; i < TN; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(ws + i * 32 * LDS_STRIDE + ks * 16);
-#pragma unroll
-      for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) store_lds(buf ^ 1);
+  for (int kt = 0; kt < nk; kt += 2) {
+    SPECA_COMPUTE(0);                      // tile kt
+    SPECA_STOREL(ra1, rw1, 1);             // tile kt+1 -> buffer 1
+    SPECA_LOADG(ra1, rw1, kt + 3);
+    __syncthreads();
+    if (kt + 1 < nk) SPECA_COMPUTE(1);     // tile kt+1
+    SPECA_STOREL(ra0, rw0, 0);             // tile kt+2 -> buffer 0
+    SPECA_LOADG(ra0, rw0, kt + 4);
     __syncthreads();
   }
+#undef SPECA_LOADG
+#undef SPECA_STOREL
+#undef SPECA_COMPUTE
 
   // epilogue.  acc[i][j][4*jj + ii] = C[m][n] with m = wm*WM + j*32 + l32, n = wn*WN + i*32 + 8*jj + 4*lhi + ii
   // inside the tile.  The tile goes through LDS once (fp32, rows padded by 16 bytes: conflict-free for
@@ -136,7 +179,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
       }
   __syncthreads();
   constexpr int QPR = BN / 4;                        // quads per row
-  constexpr int RPP = 256 / QPR;                     // rows per pass
+  constexpr int RPP = NT / QPR;                      // rows per pass
   const int qc = (tid % QPR) * 4, qr = tid / QPR;
 #pragma unroll 4
   for (int r = qr; r < BM; r += RPP) {
@@ -149,26 +192,33 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
   }
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int WGM, int WGN>
 Error launch_tile(const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi, hipStream_t st) {
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const int64_t nblk = static_cast<int64_t>(tiles_m) * tiles_n;
-  if (nblk > 0x7FFFFFFF) SPECA_FAIL(SPECA_EINVAL, "gemm: too many tiles");
+  if (nblk > 0x7FFFFFF0) SPECA_FAIL(SPECA_EINVAL, "gemm: too many tiles");
   const size_t smem_ops = static_cast<size_t>(2) * (BM + BN) * LDS_STRIDE * sizeof(uint16_t);
   const size_t smem_epi = static_cast<size_t>(BM) * (BN + 4) * sizeof(float);
   const size_t smem = smem_ops > smem_epi ? smem_ops : smem_epi;
   const uint16_t* a = static_cast<const uint16_t*>(A);
   const uint16_t* w = static_cast<const uint16_t*>(W);
   dim3 grid(static_cast<unsigned>((nblk + 7) / 8 * 8));
-#define SPECA_LAUNCH(MODE_)                                                                                      \
+  const int group_m = tiles_m < 4 ? tiles_m : 4;
+  const bool ktail = K % BK != 0;
+#define SPECA_LAUNCH2(MODE_, KT_)                                                                               \
   {                                                                                                              \
-    auto kern = gemm_mfma_kernel<BM, BN, MODE_>;                                                                 \
+    auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, MODE_, KT_>;                                                  \
     static bool attr_set = false;   /* more than 64 KB of dynamic LDS must be requested once per kernel */         \
     if (smem > 64 * 1024 && !attr_set) {                                                                         \
       SPECA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem))); \
       attr_set = true;                                                                                           \
     }                                                                                                            \
-    kern<<<grid, 256, smem, st>>>(a, lda, w, ldw, M, N, K, tiles_m, tiles_n, epi);                               \
+    kern<<<grid, WGM * WGN * 64, smem, st>>>(a, lda, w, ldw, M, N, K, tiles_m, tiles_n, group_m, epi);            \
+  }
+#define SPECA_LAUNCH(MODE_)                       \
+  {                                               \
+    if (ktail) SPECA_LAUNCH2(MODE_, true)         \
+    else SPECA_LAUNCH2(MODE_, false)              \
   }
   switch (epi.mode) {
     case EPI_STORE: SPECA_LAUNCH(EPI_STORE) break;
@@ -179,6 +229,7 @@ Error launch_tile(const void* A, int64_t lda, const void* W, int64_t ldw, int M,
     default: SPECA_FAIL(SPECA_EINVAL, "gemm: epilogue mode %d", epi.mode);
   }
 #undef SPECA_LAUNCH
+#undef SPECA_LAUNCH2
   SPECA_HIP(hipGetLastError());
   return ok();
 }
@@ -191,11 +242,17 @@ bool gemm_mfma_supported(const void* A, int64_t lda, const void* W, int64_t ldw,
 }
 
 Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi, hipStream_t st) {
-  // 128x128 tiles (measured faster than 128x64 even at 288 tiles: half the operand traffic per
-  // FLOP); 128x64 only for problems too small to give each CU a tile otherwise
+  // Tile shapes, from measurements on the reference-step shapes (M = 4096, N 1152..4608):
+  //   256x128 with 8 waves (4x2, wave tile 64x64): three quarters of the operand traffic per FLOP of
+  //     a 128x128 tile at the same per-wave register cost; best when it still leaves >= 1 tile per
+  //     CU-half and N is not so wide that 128x128 already fills the chip several times over;
+  //   128x128 with 4 waves: the default for everything else that is big enough;
+  //   128x64: problems too small to give each CU a tile otherwise.
   const int64_t t128 = static_cast<int64_t>((M + 127) / 128) * ((N + 127) / 128);
-  if (t128 >= 200) return launch_tile<128, 128>(A, lda, W, ldw, M, N, K, epi, st);
-  return launch_tile<128, 64>(A, lda, W, ldw, M, N, K, epi, st);
+  const int64_t t256 = static_cast<int64_t>((M + 255) / 256) * ((N + 127) / 128);
+  if (t256 >= 128 && t128 <= 1024 && M >= 256) return launch_tile<256, 128, 4, 2>(A, lda, W, ldw, M, N, K, epi, st);
+  if (t128 >= 200) return launch_tile<128, 128, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
+  return launch_tile<128, 64, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
 }
 
 }  // namespace speca
