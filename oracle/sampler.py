@@ -103,10 +103,15 @@ class Trace:
 # ----------------------------------------------------------------------------- one sample
 
 
-def _rows_for_sample(model, solver: Solver, label: int):
+def _rows_for_sample(model, solver: Solver, cond):
+    """Conditioning of the rows of one sample.  Class-conditional models: `cond` is the label;
+    with guidance a second row carries the null label.  Models with their own `rows_cond`
+    (text-conditioned) take `cond` as is."""
+    if hasattr(model, "rows_cond"):
+        return model.rows_cond(cond, solver.cfg_scale > 0)
     if solver.cfg_scale > 0:
-        return [int(label), int(model.s.num_classes)]      # conditional row, null-label row
-    return [int(label)]
+        return [int(cond), int(model.s.num_classes)]       # conditional row, null-label row
+    return [int(cond)]
 
 
 def _model_out(out_rows, solver: Solver):
@@ -145,11 +150,11 @@ def speculative_attempt(model, cache: core.FeatureCache, cfg: SpecaConfig, x_row
     return True, errs, model.finish(h, c)
 
 
-def sample_one(model, cfg: SpecaConfig, solver: Solver, tau: np.ndarray, x0: np.ndarray, label: int):
-    """Whole trajectory of one sample.  x0: [C,H,W].  -> (final latent, kinds[S], errs[S,rows])."""
+def sample_one(model, cfg: SpecaConfig, solver: Solver, tau: np.ndarray, x0: np.ndarray, label):
+    """Whole trajectory of one sample.  x0: [C,(T,)H,W].  -> (final latent, kinds[S], errs[S,rows])."""
     S = solver.steps
     labels = _rows_for_sample(model, solver, label)
-    R = len(labels)
+    R = 2 if solver.cfg_scale > 0 else 1
     cache = core.FeatureCache(model.n_slots, cfg.order, cfg.mode, cfg.cache_store)
     x = np.asarray(x0, dtype=np.float64)
     kinds = np.zeros(S, dtype=np.int8)
@@ -179,7 +184,7 @@ def sample(model, cfg: SpecaConfig, solver: Solver, tau: np.ndarray, latents: np
     out = np.empty(latents.shape, dtype=np.float64)
     tr = Trace(np.zeros((B, S), np.int8), np.full((B, S, R), np.nan, np.float32), np.asarray(tau, np.float32))
     for b in range(B):
-        out[b], tr.kind[b], tr.err[b] = sample_one(model, cfg, solver, tr.tau, latents[b], int(labels[b]))
+        out[b], tr.kind[b], tr.err[b] = sample_one(model, cfg, solver, tr.tau, latents[b], labels[b])
     return out, tr
 
 
@@ -189,9 +194,10 @@ def sample_plain(model, solver: Solver, latents: np.ndarray, labels: Sequence[in
     out = np.empty(latents.shape, dtype=np.float64)
     for b in range(B):
         x = np.asarray(latents[b], dtype=np.float64)
-        lab = _rows_for_sample(model, solver, int(labels[b]))
+        lab = _rows_for_sample(model, solver, labels[b])
+        R = 2 if solver.cfg_scale > 0 else 1
         for s in range(solver.steps):
-            o, _ = model.forward(np.repeat(x[None], len(lab), axis=0), float(solver.timesteps[s]), lab)
+            o, _ = model.forward(np.repeat(x[None], R, axis=0), float(solver.timesteps[s]), lab)
             x = solver.update(x, _model_out(o, solver), s)
         out[b] = x
     return out

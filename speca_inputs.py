@@ -251,3 +251,145 @@ def perturbed_target(pred: np.ndarray, deltas, seed: int = 0, dtype: str = "bf16
         rms = float(np.sqrt(np.mean(pred[b].astype(np.float64) ** 2)))
         out[b] = pred[b] + np.float32(deltas[b % len(deltas)] * rms) * z
     return _store(out, dtype)
+
+
+# ----------------------------------------------------------------------------- MMDiT
+
+
+@dataclass(frozen=True)
+class MMDiTShape:
+    """Rectified-flow MMDiT (shape only): dual-stream blocks over (text, image) tokens with
+    joint attention, then single-stream blocks over the concatenated sequence; rotary
+    positions; per-head RMS-norm on q and k."""
+    depth_dual: int
+    depth_single: int
+    hidden: int            # D
+    heads: int             # head_dim = D / heads
+    mlp_hidden: int        # Dm
+    in_channels: int       # latent channels C
+    latent_t: int          # latent frames (1 = image)
+    latent_h: int
+    latent_w: int
+    patch: int             # spatial patch (temporal patch is 1)
+    txt_tokens: int
+    txt_dim: int
+    vec_dim: int
+    rope_axes: Tuple[int, int, int]   # head_dim split over (t, y, x); sums to head_dim
+    freq_dim: int = 256
+    dtype: str = "bf16"
+
+    @property
+    def head_dim(self) -> int:
+        return self.hidden // self.heads
+
+    @property
+    def img_tokens(self) -> int:
+        return self.latent_t * (self.latent_h // self.patch) * (self.latent_w // self.patch)
+
+    @property
+    def tokens(self) -> int:
+        return self.txt_tokens + self.img_tokens
+
+    @property
+    def patch_dim(self) -> int:
+        return self.in_channels * self.patch * self.patch
+
+    @property
+    def n_slots(self) -> int:
+        return 2 * self.depth_dual + self.depth_single
+
+    @property
+    def mod_width(self) -> int:
+        return self.depth_dual * 12 * self.hidden + self.depth_single * 3 * self.hidden + 2 * self.hidden
+
+
+def mmdit_tiny(dtype: str = "f32") -> MMDiTShape:
+    """Reduced MMDiT for end-to-end parity (the full shapes are far beyond a CPU oracle)."""
+    return MMDiTShape(depth_dual=2, depth_single=2, hidden=128, heads=2, mlp_hidden=512, in_channels=4, latent_t=1,
+                      latent_h=8, latent_w=12, patch=2, txt_tokens=8, txt_dim=32, vec_dim=24, rope_axes=(16, 24, 24),
+                      freq_dim=32, dtype=dtype)
+
+
+def mmdit_tiny_video(dtype: str = "f32") -> MMDiTShape:
+    return MMDiTShape(depth_dual=1, depth_single=2, hidden=128, heads=2, mlp_hidden=512, in_channels=4, latent_t=3,
+                      latent_h=4, latent_w=8, patch=2, txt_tokens=5, txt_dim=32, vec_dim=24, rope_axes=(16, 24, 24),
+                      freq_dim=32, dtype=dtype)
+
+
+def mmdit_flux(dtype: str = "bf16") -> MMDiTShape:
+    """Configuration 4: FLUX-shaped, 1024x1024 (latent 16 x 128 x 128, patch 2 -> 4096 tokens), 512 text tokens."""
+    return MMDiTShape(depth_dual=19, depth_single=38, hidden=3072, heads=24, mlp_hidden=12288, in_channels=16, latent_t=1,
+                      latent_h=128, latent_w=128, patch=2, txt_tokens=512, txt_dim=4096, vec_dim=768, rope_axes=(16, 56, 56),
+                      dtype=dtype)
+
+
+def mmdit_hunyuan(dtype: str = "bf16") -> MMDiTShape:
+    """Configuration 5: HunyuanVideo-shaped, 480p 2 s (latent 16 x 17 x 60 x 106, patch 1x2x2 -> 27030 tokens), 256 text tokens."""
+    return MMDiTShape(depth_dual=20, depth_single=40, hidden=3072, heads=24, mlp_hidden=12288, in_channels=16, latent_t=17,
+                      latent_h=60, latent_w=106, patch=2, txt_tokens=256, txt_dim=4096, vec_dim=768, rope_axes=(16, 56, 56),
+                      dtype=dtype)
+
+
+def rope_tables(s: MMDiTShape, theta: float = 10000.0) -> Tuple[np.ndarray, np.ndarray]:
+    """cos/sin tables [tokens, head_dim/2] of the rotary embedding: text tokens sit at the
+    origin, image token (f, i, j) at position (f, i, j); axis a owns rope_axes[a]/2 frequency
+    pairs with omega_q = theta^(-2q/rope_axes[a])."""
+    assert sum(s.rope_axes) == s.head_dim and all(a % 2 == 0 for a in s.rope_axes)
+    gh, gw = s.latent_h // s.patch, s.latent_w // s.patch
+    f, i, j = np.meshgrid(np.arange(s.latent_t), np.arange(gh), np.arange(gw), indexing="ij")
+    ids = np.stack([f.ravel(), i.ravel(), j.ravel()], axis=1).astype(np.float64)
+    ids = np.concatenate([np.zeros((s.txt_tokens, 3)), ids], axis=0)
+    ang = []
+    for a, d in enumerate(s.rope_axes):
+        omega = 1.0 / theta ** (np.arange(0, d, 2, dtype=np.float64) / d)
+        ang.append(ids[:, a:a + 1] * omega[None, :])
+    ang = np.concatenate(ang, axis=1)
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
+def mmdit_param_shapes(s: MMDiTShape) -> Dict[str, Tuple[int, ...]]:
+    D, Dm, hd = s.hidden, s.mlp_hidden, s.head_dim
+    shp = {
+        "t_w1": (D, s.freq_dim), "t_b1": (D,), "t_w2": (D, D), "t_b2": (D,),
+        "v_w1": (D, s.vec_dim), "v_b1": (D,), "v_w2": (D, D), "v_b2": (D,),
+        "img_in_w": (D, s.patch_dim), "img_in_b": (D,), "txt_in_w": (D, s.txt_dim), "txt_in_b": (D,),
+        "fmod_w": (2 * D, D), "fmod_b": (2 * D,), "final_w": (s.patch_dim, D), "final_b": (s.patch_dim,),
+    }
+    for l in range(s.depth_dual):
+        for st in ("img", "txt"):
+            p = f"dual{l}.{st}_"
+            shp.update({p + "mod_w": (6 * D, D), p + "mod_b": (6 * D,), p + "qkv_w": (3 * D, D), p + "qkv_b": (3 * D,),
+                        p + "qnorm": (hd,), p + "knorm": (hd,), p + "proj_w": (D, D), p + "proj_b": (D,),
+                        p + "fc1_w": (Dm, D), p + "fc1_b": (Dm,), p + "fc2_w": (D, Dm), p + "fc2_b": (D,)})
+    for l in range(s.depth_single):
+        p = f"single{l}."
+        shp.update({p + "mod_w": (3 * D, D), p + "mod_b": (3 * D,), p + "lin1_w": (3 * D + Dm, D), p + "lin1_b": (3 * D + Dm,),
+                    p + "qnorm": (hd,), p + "knorm": (hd,), p + "lin2_w": (D, D + Dm), p + "lin2_b": (D,)})
+    return shp
+
+
+def make_mmdit_weights(s: MMDiTShape, seed: int = 0, std: float = 0.02) -> Dict[str, np.ndarray]:
+    """All parameters ~ N(0, std^2) in dict order of mmdit_param_shapes (stream (seed, 4, k)),
+    except the RMS-norm scales which are 1 + N(0, std^2); plus the rotary tables
+    "rope_cos"/"rope_sin" (float32, not rounded)."""
+    out: Dict[str, np.ndarray] = {}
+    for k, (name, shape) in enumerate(mmdit_param_shapes(s).items()):
+        a = _rng(seed, 4, k).standard_normal(shape, dtype=np.float32) * np.float32(std)
+        if name.endswith("norm"):
+            a = a + np.float32(1.0)
+        out[name] = _store(a, s.dtype)
+    out["rope_cos"], out["rope_sin"] = rope_tables(s)
+    return out
+
+
+def make_text(batch: int, s: MMDiTShape, seed: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    """Stand-ins for the text encoder outputs: token embeddings [batch, txt_tokens, txt_dim]
+    and pooled vector [batch, vec_dim], N(0,1), stored in the model dtype."""
+    txt = _rng(seed, 5).standard_normal((batch, s.txt_tokens, s.txt_dim), dtype=np.float32)
+    vec = _rng(seed, 6).standard_normal((batch, s.vec_dim), dtype=np.float32)
+    return _store(txt, s.dtype), _store(vec, s.dtype)
+
+
+def make_video_latents(batch: int, s: MMDiTShape, seed: int = 0) -> np.ndarray:
+    """Initial noise N(0,1), float32 [batch, C, T, H, W]."""
+    return _rng(seed, 2).standard_normal((batch, s.in_channels, s.latent_t, s.latent_h, s.latent_w), dtype=np.float32)
