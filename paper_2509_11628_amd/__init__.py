@@ -3,4 +3,4 @@ ctypes binding.  Importing the package does not load the library; the first call
 it fails loudly if the library has not been built."""
 from . import binding  # noqa: F401
 from .binding import (Context, Scheduler, SpecaError, load_library, make_cfg, cache_only_desc,  # noqa: F401
-                      dit_desc, to_device)
+                      dit_desc, mmdit_desc, to_device)

@@ -392,10 +392,25 @@ def dit_desc(shape, dtype: Optional[int] = None) -> ModelDesc:
     return d
 
 
+FP32_TABLES = ("rope_cos", "rope_sin")     # tables the library reads as float32 whatever the model dtype
+
+
 def to_device(arrays: Dict[str, np.ndarray], dtype: int, device="cuda") -> Dict[str, "object"]:
     """NumPy float32 arrays -> contiguous device tensors of the model dtype (exact when the
-    values are already representable)."""
+    values are already representable); the rotary tables stay float32."""
     import torch
     td = _torch_dtype(dtype)
-    return {k: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(device=device, dtype=td).contiguous()
+    return {k: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(device=device, dtype=torch.float32 if k in FP32_TABLES else td).contiguous()
             for k, v in arrays.items()}
+
+
+def mmdit_desc(shape, dtype: Optional[int] = None) -> ModelDesc:
+    """shape: an object with the fields of speca_inputs.MMDiTShape."""
+    d = ModelDesc()
+    d.kind = MODEL_MMDIT
+    d.dtype = dtype if dtype is not None else (BF16 if shape.dtype == "bf16" else F32)
+    d.depth, d.depth_single = shape.depth_dual, shape.depth_single
+    d.hidden, d.heads, d.mlp_hidden = shape.hidden, shape.heads, shape.mlp_hidden
+    d.in_channels, d.latent_t, d.latent_h, d.latent_w, d.patch = shape.in_channels, shape.latent_t, shape.latent_h, shape.latent_w, shape.patch
+    d.freq_dim, d.txt_tokens, d.txt_dim, d.vec_dim = shape.freq_dim, shape.txt_tokens, shape.txt_dim, shape.vec_dim
+    return d

@@ -131,7 +131,8 @@ static Error create_impl(speca_ctx** out, const speca_model_desc* desc, const sp
       SPECA_TRY(make_dit_model(*desc, w, &ctx->model));
       break;
     case SPECA_MODEL_MMDIT:
-      SPECA_FAIL(SPECA_EUNSUPPORTED, "MMDiT models are not built into this library yet");
+      SPECA_TRY(make_mmdit_model(*desc, w, &ctx->model));
+      break;
     default:
       SPECA_FAIL(SPECA_EINVAL, "model kind = %d", desc->kind);
   }
@@ -371,7 +372,7 @@ int speca_linear(void* hip_stream, int dtype, const void* a, int m, int k, const
 
 int speca_attention(void* hip_stream, int dtype, const void* qkv, void* out, int rows, int tokens, int heads, int head_dim) {
   if (dtype != SPECA_F32 && dtype != SPECA_BF16) { g_create_error = "dtype"; return SPECA_EINVAL; }
-  Error r = launch_attention(dtype, qkv, out, rows, tokens, heads, head_dim, static_cast<hipStream_t>(hip_stream));
+  Error r = launch_attention(dtype, qkv, out, static_cast<int64_t>(heads) * head_dim, rows, tokens, heads, head_dim, static_cast<hipStream_t>(hip_stream));
   if (r.code != SPECA_OK) g_create_error = r.msg;
   return r.code;
 }

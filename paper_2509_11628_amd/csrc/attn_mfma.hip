@@ -34,8 +34,8 @@ __device__ inline uint32_t pack_bf16(float a, float b) {
 }
 
 template <int HD>
-__global__ __launch_bounds__(256) void attention_mfma_kernel(const uint16_t* __restrict__ qkv, uint16_t* __restrict__ out, int T,
-                                                             int H, float scale_log2e) {
+__global__ __launch_bounds__(256) void attention_mfma_kernel(const uint16_t* __restrict__ qkv, uint16_t* __restrict__ out, int64_t ldo,
+                                                             int T, int H, float scale_log2e) {
   constexpr int HD16 = (HD + 15) / 16 * 16, HD32 = (HD + 31) / 32 * 32;
   constexpr int KS = HD16 / 16;         // reduction steps of q k^T
   constexpr int DT = HD32 / 32;         // 32-row tiles of O^T
@@ -204,7 +204,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const uint16_t* __r
   const float inv = 1.0f / ltot;
   const int q = q0 + wave * 32 + l32;
   if (q < T) {
-    uint16_t* op = out + (static_cast<int64_t>(row) * T + q) * D + head * HD;
+    uint16_t* op = out + (static_cast<int64_t>(row) * T + q) * ldo + head * HD;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const uint16_t* __r
 }
 
 template <int HD>
-Error launch_hd(const void* qkv, void* out, int rows, int T, int H, hipStream_t st) {
+Error launch_hd(const void* qkv, void* out, int64_t ldo, int rows, int T, int H, hipStream_t st) {
   constexpr int HD16 = (HD + 15) / 16 * 16, HD32 = (HD + 31) / 32 * 32;
   const size_t smem = static_cast<size_t>(2) * (64 * (HD16 + 8) + HD32 * (64 + 8)) * sizeof(uint16_t);
   auto kern = attention_mfma_kernel<HD>;
@@ -232,23 +232,23 @@ Error launch_hd(const void* qkv, void* out, int rows, int T, int H, hipStream_t 
   }
   dim3 grid((T + 127) / 128, H, rows);
   const float scale_log2e = 1.4426950408889634f / sqrtf(static_cast<float>(HD));
-  kern<<<grid, 256, smem, st>>>(static_cast<const uint16_t*>(qkv), static_cast<uint16_t*>(out), T, H, scale_log2e);
+  kern<<<grid, 256, smem, st>>>(static_cast<const uint16_t*>(qkv), static_cast<uint16_t*>(out), ldo, T, H, scale_log2e);
   SPECA_HIP(hipGetLastError());
   return ok();
 }
 
 }  // namespace
 
-bool attention_mfma_supported(const void* qkv, const void* out, int H, int hd) {
-  return (hd == 64 || hd == 72 || hd == 128) && reinterpret_cast<uintptr_t>(qkv) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 8 == 0;
+bool attention_mfma_supported(const void* qkv, const void* out, int64_t ldo, int H, int hd) {
+  return (hd == 64 || hd == 72 || hd == 128) && ldo % 4 == 0 && reinterpret_cast<uintptr_t>(qkv) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 8 == 0;
 }
 
-Error launch_attention_mfma(const void* qkv, void* out, int rows, int T, int H, int hd, hipStream_t st) {
+Error launch_attention_mfma(const void* qkv, void* out, int64_t ldo, int rows, int T, int H, int hd, hipStream_t st) {
   if (rows > 65535 || H > 65535) SPECA_FAIL(SPECA_EINVAL, "attention: grid too large");
   switch (hd) {
-    case 64: return launch_hd<64>(qkv, out, rows, T, H, st);
-    case 72: return launch_hd<72>(qkv, out, rows, T, H, st);
-    case 128: return launch_hd<128>(qkv, out, rows, T, H, st);
+    case 64: return launch_hd<64>(qkv, out, ldo, rows, T, H, st);
+    case 72: return launch_hd<72>(qkv, out, ldo, rows, T, H, st);
+    case 128: return launch_hd<128>(qkv, out, ldo, rows, T, H, st);
   }
   SPECA_FAIL(SPECA_EUNSUPPORTED, "attention: head_dim %d has no MFMA kernel", hd);
 }

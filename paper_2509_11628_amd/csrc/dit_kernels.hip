@@ -66,12 +66,14 @@ __global__ void patch_embed_kernel(const float* __restrict__ x, RowLabels xrow, 
 // Statistics in fp32, two passes over registers.
 template <typename T, int PER_LANE>
 __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restrict__ h, const float* __restrict__ shift,
-                                                          const float* __restrict__ scale, int64_t mod_stride, T* __restrict__ y,
-                                                          int64_t n_tokens, int tokens_per_row, int D) {
+                                                          const float* __restrict__ scale, const float* __restrict__ shift2,
+                                                          const float* __restrict__ scale2, int split_tok, int64_t mod_stride,
+                                                          T* __restrict__ y, int64_t n_tokens, int tokens_per_row, int D) {
   const int64_t tok = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
   if (tok >= n_tokens) return;
   const int lane = threadIdx.x & 63;
   const int i = static_cast<int>(tok / tokens_per_row);
+  const bool second = static_cast<int>(tok - static_cast<int64_t>(i) * tokens_per_row) >= split_tok;   // tokens from split_tok on use the second set
   const float* hp = h + tok * D;
   float v[PER_LANE];
   float s = 0.0f;
@@ -94,8 +96,8 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) q += __shfl_xor(q, off, 64);
   const float rstd = rsqrtf(q / static_cast<float>(D) + 1e-6f);
-  const float* sh = shift + static_cast<int64_t>(i) * mod_stride;
-  const float* sc = scale + static_cast<int64_t>(i) * mod_stride;
+  const float* sh = (second ? shift2 : shift) + static_cast<int64_t>(i) * mod_stride;
+  const float* sc = (second ? scale2 : scale) + static_cast<int64_t>(i) * mod_stride;
   T* yp = y + tok * D;
 #pragma unroll
   for (int j = 0; j < PER_LANE; ++j) {
@@ -106,12 +108,13 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
 
 // Speculative step: h_out[i][e] = h_in[i][e] + sum_{slot in [s0,s1)} gate_slot[i][d] * sum_o c[i][o] D^o[slot][row_i][e]
 // (Eq. 2 for every slot, folded into the residual stream; only the hidden state is written).
-// gate of slot j for compact row i: mod[i * mod_stride + gate_off[j] + d].
+// gate of slot j for compact row i: mod[i * mod_stride + gate_off[2j + s] + d], s = 0 for elements below
+// split_elem (the text tokens of a two-stream block), 1 from there on.
 template <typename T, int NT>
 __global__ __launch_bounds__(256) void forecast_fold_kernel(CacheGeom g, RowTable rt, const float* __restrict__ h_in,
                                                             float* __restrict__ h_out, const float* __restrict__ mod,
-                                                            int64_t mod_stride, const int32_t* __restrict__ gate_off, int s0, int s1,
-                                                            int D) {
+                                                            int64_t mod_stride, const int32_t* __restrict__ gate_off, int64_t split_elem,
+                                                            int s0, int s1, int D) {
   constexpr int V = 4;     // 4 elements per thread: 16 B of fp32 hidden, 8 B (bf16) or 16 B (fp32) of cache
   const int i = blockIdx.y;
   const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * V;
@@ -127,7 +130,7 @@ __global__ __launch_bounds__(256) void forecast_fold_kernel(CacheGeom g, RowTabl
   float acc[V] = {hv.x, hv.y, hv.z, hv.w};
   const float* mrow = mod + static_cast<int64_t>(i) * mod_stride + d;
   for (int slot = s0; slot < s1; ++slot) {
-    const float4 gv = *reinterpret_cast<const float4*>(mrow + gate_off[slot]);
+    const float4 gv = *reinterpret_cast<const float4*>(mrow + gate_off[2 * slot + (e >= split_elem ? 1 : 0)]);
     const float gg[V] = {gv.x, gv.y, gv.z, gv.w};
     float f[V] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
@@ -203,15 +206,15 @@ Error launch_patch_embed(int dtype, const float* x, const RowLabels& xrow, const
 }
 
 template <typename T>
-static Error ln_mod_t(const float* h, const float* shift, const float* scale, int64_t mod_stride, void* y, int64_t n_tokens,
-                      int tokens_per_row, int D, hipStream_t st) {
+static Error ln_mod_t(const float* h, const float* shift, const float* scale, const float* shift2, const float* scale2, int split_tok,
+                      int64_t mod_stride, void* y, int64_t n_tokens, int tokens_per_row, int D, hipStream_t st) {
   const unsigned grid = blocks_for(n_tokens, 4);
   T* yp = static_cast<T*>(y);
   const int per = (D + 63) / 64;
-  if (per <= 1) ln_modulate_kernel<T, 1><<<grid, 256, 0, st>>>(h, shift, scale, mod_stride, yp, n_tokens, tokens_per_row, D);
-  else if (per <= 4) ln_modulate_kernel<T, 4><<<grid, 256, 0, st>>>(h, shift, scale, mod_stride, yp, n_tokens, tokens_per_row, D);
-  else if (per <= 18) ln_modulate_kernel<T, 18><<<grid, 256, 0, st>>>(h, shift, scale, mod_stride, yp, n_tokens, tokens_per_row, D);
-  else if (per <= 48) ln_modulate_kernel<T, 48><<<grid, 256, 0, st>>>(h, shift, scale, mod_stride, yp, n_tokens, tokens_per_row, D);
+  if (per <= 1) ln_modulate_kernel<T, 1><<<grid, 256, 0, st>>>(h, shift, scale, shift2, scale2, split_tok, mod_stride, yp, n_tokens, tokens_per_row, D);
+  else if (per <= 4) ln_modulate_kernel<T, 4><<<grid, 256, 0, st>>>(h, shift, scale, shift2, scale2, split_tok, mod_stride, yp, n_tokens, tokens_per_row, D);
+  else if (per <= 18) ln_modulate_kernel<T, 18><<<grid, 256, 0, st>>>(h, shift, scale, shift2, scale2, split_tok, mod_stride, yp, n_tokens, tokens_per_row, D);
+  else if (per <= 48) ln_modulate_kernel<T, 48><<<grid, 256, 0, st>>>(h, shift, scale, shift2, scale2, split_tok, mod_stride, yp, n_tokens, tokens_per_row, D);
   else SPECA_FAIL(SPECA_EUNSUPPORTED, "LayerNorm: hidden %d > 3072", D);
   SPECA_HIP(hipGetLastError());
   return ok();
@@ -219,34 +222,40 @@ static Error ln_mod_t(const float* h, const float* shift, const float* scale, in
 
 Error launch_ln_modulate(int dtype, const float* h, const float* shift, const float* scale, int64_t mod_stride, void* y,
                          int64_t n_tokens, int tokens_per_row, int D, hipStream_t st) {
-  return dtype == SPECA_BF16 ? ln_mod_t<bf16_t>(h, shift, scale, mod_stride, y, n_tokens, tokens_per_row, D, st)
-                             : ln_mod_t<float>(h, shift, scale, mod_stride, y, n_tokens, tokens_per_row, D, st);
+  return launch_ln_modulate2(dtype, h, shift, scale, shift, scale, tokens_per_row, mod_stride, y, n_tokens, tokens_per_row, D, st);
+}
+
+Error launch_ln_modulate2(int dtype, const float* h, const float* shift, const float* scale, const float* shift2, const float* scale2,
+                          int split_tok, int64_t mod_stride, void* y, int64_t n_tokens, int tokens_per_row, int D, hipStream_t st) {
+  return dtype == SPECA_BF16 ? ln_mod_t<bf16_t>(h, shift, scale, shift2, scale2, split_tok, mod_stride, y, n_tokens, tokens_per_row, D, st)
+                             : ln_mod_t<float>(h, shift, scale, shift2, scale2, split_tok, mod_stride, y, n_tokens, tokens_per_row, D, st);
 }
 
 template <typename T>
 static Error fold_t(const CacheGeom& g, const RowTable& rt, const float* h_in, float* h_out, const float* mod, int64_t mod_stride,
-                    const int32_t* gate_off, int s0, int s1, int D, hipStream_t st) {
+                    const int32_t* gate_off, int64_t split_elem, int s0, int s1, int D, hipStream_t st) {
   int mo = 0;
   for (int i = 0; i < rt.n; ++i) mo = rt.order[i] > mo ? rt.order[i] : mo;
   dim3 grid(blocks_for(g.E, 256 * 4), rt.n);
   switch (mo) {
-    case 0: forecast_fold_kernel<T, 1><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, s0, s1, D); break;
-    case 1: forecast_fold_kernel<T, 2><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, s0, s1, D); break;
-    case 2: forecast_fold_kernel<T, 3><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, s0, s1, D); break;
-    case 3: forecast_fold_kernel<T, 4><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, s0, s1, D); break;
-    default: forecast_fold_kernel<T, 5><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, s0, s1, D); break;
+    case 0: forecast_fold_kernel<T, 1><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, split_elem, s0, s1, D); break;
+    case 1: forecast_fold_kernel<T, 2><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, split_elem, s0, s1, D); break;
+    case 2: forecast_fold_kernel<T, 3><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, split_elem, s0, s1, D); break;
+    case 3: forecast_fold_kernel<T, 4><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, split_elem, s0, s1, D); break;
+    default: forecast_fold_kernel<T, 5><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, split_elem, s0, s1, D); break;
   }
   SPECA_HIP(hipGetLastError());
   return ok();
 }
 
 Error launch_forecast_fold(const CacheGeom& g, const RowTable& rt, const float* h_in, float* h_out, const float* mod,
-                           int64_t mod_stride, const int32_t* gate_off_dev, int s0, int s1, int D, hipStream_t st) {
+                           int64_t mod_stride, const int32_t* gate_off_dev, int64_t split_elem, int s0, int s1, int D, hipStream_t st) {
   if (rt.n <= 0 || rt.n > kMaxRows) SPECA_FAIL(SPECA_EINVAL, "forecast_fold: %d rows", rt.n);
   if (g.E % 4 || D % 4) SPECA_FAIL(SPECA_EUNSUPPORTED, "forecast_fold needs hidden %% 4 == 0");
   if (s0 < 0 || s1 > g.n_slots || s0 > s1) SPECA_FAIL(SPECA_EINVAL, "forecast_fold: slots [%d,%d)", s0, s1);
-  return g.dtype == SPECA_BF16 ? fold_t<bf16_t>(g, rt, h_in, h_out, mod, mod_stride, gate_off_dev, s0, s1, D, st)
-                               : fold_t<float>(g, rt, h_in, h_out, mod, mod_stride, gate_off_dev, s0, s1, D, st);
+  if (split_elem < 0 || split_elem % 4) SPECA_FAIL(SPECA_EINVAL, "forecast_fold: split");
+  return g.dtype == SPECA_BF16 ? fold_t<bf16_t>(g, rt, h_in, h_out, mod, mod_stride, gate_off_dev, split_elem, s0, s1, D, st)
+                               : fold_t<float>(g, rt, h_in, h_out, mod, mod_stride, gate_off_dev, split_elem, s0, s1, D, st);
 }
 
 Error launch_unpatchify(const float* tok, const RowLabels& rows, float* out, int n, int C, int Hh, int Ww, int p, hipStream_t st) {

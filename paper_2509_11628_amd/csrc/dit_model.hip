@@ -39,7 +39,7 @@ struct DiT final : Model {
   void* mod_w = nullptr;
   void* mod_b = nullptr;
   int64_t mod_n = 0;                 // L*6D + 2D
-  int32_t* gate_off_dev = nullptr;   // [2L] offset of each slot's gate inside a modulation row
+  int32_t* gate_off_dev = nullptr;   // [2L][2] offset of each slot's gate inside a modulation row
   // workspace for up to cap_rows rows
   int cap_rows = 0;
   void *emb = nullptr, *t_hid = nullptr, *sc = nullptr, *xn = nullptr, *qkv = nullptr, *att = nullptr, *f1 = nullptr;
@@ -134,7 +134,7 @@ struct DiT final : Model {
     }
     {
       ProfScope ps(ctx, SPECA_PROF_ATTENTION, 4.0 * n * H * static_cast<double>(T) * T * hd, Md * 4 * D * esz);
-      SPECA_TRY(launch_attention(d.dtype, qkv, att, n, T, H, hd, st));
+      SPECA_TRY(launch_attention(d.dtype, qkv, att, D, n, T, H, hd, st));
     }
     GemmEpi b;
     b.mode = EPI_BRANCH; b.bias = blk[l].proj_b; b.h = hs; b.ldh = D; b.gate = mod_at(l, 2); b.gate_stride = mod_n; b.tokens = T;
@@ -227,12 +227,12 @@ struct DiT final : Model {
     const double tens = table_tensors(rt), Ed = static_cast<double>(ctx->geom.E);
     {
       ProfScope ps(ctx, SPECA_PROF_FORECAST, 0.0, 2.0 * lv * tens * Ed * esz + 2.0 * n * Ed * 4);
-      SPECA_TRY(launch_forecast_fold(ctx->geom, rt, h, h, mod, mod_n, gate_off_dev, 0, 2 * lv, D, st));
+      SPECA_TRY(launch_forecast_fold(ctx->geom, rt, h, h, mod, mod_n, gate_off_dev, 0, 0, 2 * lv, D, st));
     }
     // accepted path: forecasts for the verify block and everything after it -> h2
     {
       ProfScope ps(ctx, SPECA_PROF_FORECAST, 0.0, 2.0 * (L - lv) * tens * Ed * esz + 2.0 * n * Ed * 4);
-      SPECA_TRY(launch_forecast_fold(ctx->geom, rt, h, h2, mod, mod_n, gate_off_dev, 2 * lv, 2 * L, D, st));
+      SPECA_TRY(launch_forecast_fold(ctx->geom, rt, h, h2, mod, mod_n, gate_off_dev, 0, 2 * lv, 2 * L, D, st));
     }
     // the verify block for real, on h
     SPECA_TRY(attn_branch(ctx, lv, h, n, nullptr));
@@ -332,10 +332,10 @@ Error make_dit_model(const speca_model_desc& d, const speca_weights* w, std::uni
   SPECA_TRY(wl.get("fmod_b", 2 * D, &fb));
   SPECA_HIP(hipMemcpy(static_cast<char*>(m->mod_w) + static_cast<size_t>(m->L) * 6 * D * D * m->esz, fw, 2 * D * D * m->esz, hipMemcpyDeviceToDevice));
   SPECA_HIP(hipMemcpy(static_cast<char*>(m->mod_b) + static_cast<size_t>(m->L) * 6 * D * m->esz, fb, 2 * D * m->esz, hipMemcpyDeviceToDevice));
-  std::vector<int32_t> goff(2 * m->L);
+  std::vector<int32_t> goff(4 * m->L);          // [slot][2]: one stream, both entries equal
   for (int l = 0; l < m->L; ++l) {
-    goff[2 * l] = static_cast<int32_t>((static_cast<int64_t>(l) * 6 + 2) * D);
-    goff[2 * l + 1] = static_cast<int32_t>((static_cast<int64_t>(l) * 6 + 5) * D);
+    goff[4 * l] = goff[4 * l + 1] = static_cast<int32_t>((static_cast<int64_t>(l) * 6 + 2) * D);
+    goff[4 * l + 2] = goff[4 * l + 3] = static_cast<int32_t>((static_cast<int64_t>(l) * 6 + 5) * D);
   }
   SPECA_HIP(hipMalloc(reinterpret_cast<void**>(&m->gate_off_dev), goff.size() * sizeof(int32_t)));
   SPECA_HIP(hipMemcpy(m->gate_off_dev, goff.data(), goff.size() * sizeof(int32_t), hipMemcpyHostToDevice));

@@ -62,7 +62,7 @@ __device__ inline void epilogue_quad(const GemmEpi& e, int m, int n, float v[4])
     if (e.refresh) {
       // Eq. 3 as a recursion on the unrounded new values; each is rounded once when stored
       const int order = e.rt.order[i];
-      const int64_t pos = static_cast<int64_t>(t) * e.ldh + n;     // ldh == hidden == N for branch outputs
+      const int64_t pos = e.cache_elem_offset + static_cast<int64_t>(t) * e.ldh + n;     // ldh == hidden == N for branch outputs
       T* base = static_cast<T*>(e.g.base);
       float cur[4] = {v[0], v[1], v[2], v[3]};
       float old[4];

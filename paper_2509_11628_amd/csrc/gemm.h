@@ -30,6 +30,7 @@ struct GemmEpi {
   int tokens = 1;                 // tokens per row: m = i * tokens + t
   int refresh = 0;                // update cache slot `slot` for rows rt.row[i]
   int slot = 0;
+  int64_t cache_elem_offset = 0;  // added to the position inside the cache row (a launch that covers a token sub-range)
   CacheGeom g{};
   RowTable rt{};
 };
@@ -39,7 +40,7 @@ Error launch_gemm(int dtype, const void* A, int64_t lda, const void* W, int64_t 
                   hipStream_t st);
 
 // softmax(q k^T / sqrt(hd)) v without mask.  qkv: [rows][T][3][H][hd] (model dtype),
-// out: [rows][T][H*hd].
-Error launch_attention(int dtype, const void* qkv, void* out, int rows, int T, int H, int hd, hipStream_t st);
+// out: [rows][T][ldo] with the H*hd result in the first columns (ldo >= H*hd, ldo % 4 == 0).
+Error launch_attention(int dtype, const void* qkv, void* out, int64_t ldo, int rows, int T, int H, int hd, hipStream_t st);
 
 }  // namespace speca

@@ -94,8 +94,8 @@ constexpr int AT_K = 32;      // keys per LDS tile
 constexpr int HD_MAX = 128;
 
 template <typename T, int HD>
-__global__ __launch_bounds__(AT_Q) void attention_simple_kernel(const T* __restrict__ qkv, T* __restrict__ out, int Tn, int H,
-                                                                float scale) {
+__global__ __launch_bounds__(AT_Q) void attention_simple_kernel(const T* __restrict__ qkv, T* __restrict__ out, int64_t ldo, int Tn,
+                                                                int H, float scale) {
   __shared__ float Ks[AT_K][HD];
   __shared__ float Vs[AT_K][HD];
   const int row = blockIdx.z, head = blockIdx.y;
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(AT_Q) void attention_simple_kernel(const T* __restr
   }
   if (live) {
     const float inv = 1.0f / sum;
-    T* op = out + (static_cast<int64_t>(row) * Tn + qi) * D + head * HD;
+    T* op = out + (static_cast<int64_t>(row) * Tn + qi) * ldo + head * HD;
 #pragma unroll
     for (int d = 0; d < HD; ++d) {
       if (sizeof(T) == 2) reinterpret_cast<uint16_t*>(op)[d] = f32_to_bf16(o[d] * inv);
@@ -150,22 +150,22 @@ __global__ __launch_bounds__(AT_Q) void attention_simple_kernel(const T* __restr
 }
 
 template <typename T, int HD>
-Error launch_attn_t(const void* qkv, void* out, int rows, int Tn, int H, hipStream_t st) {
+Error launch_attn_t(const void* qkv, void* out, int64_t ldo, int rows, int Tn, int H, hipStream_t st) {
   dim3 grid((Tn + AT_Q - 1) / AT_Q, H, rows);
-  attention_simple_kernel<T, HD><<<grid, AT_Q, 0, st>>>(static_cast<const T*>(qkv), static_cast<T*>(out), Tn, H,
+  attention_simple_kernel<T, HD><<<grid, AT_Q, 0, st>>>(static_cast<const T*>(qkv), static_cast<T*>(out), ldo, Tn, H,
                                                         1.0f / sqrtf(static_cast<float>(HD)));
   SPECA_HIP(hipGetLastError());
   return ok();
 }
 
 template <typename T>
-Error launch_attn_hd(const void* qkv, void* out, int rows, int Tn, int H, int hd, hipStream_t st) {
+Error launch_attn_hd(const void* qkv, void* out, int64_t ldo, int rows, int Tn, int H, int hd, hipStream_t st) {
   switch (hd) {
-    case 16: return launch_attn_t<T, 16>(qkv, out, rows, Tn, H, st);
-    case 32: return launch_attn_t<T, 32>(qkv, out, rows, Tn, H, st);
-    case 64: return launch_attn_t<T, 64>(qkv, out, rows, Tn, H, st);
-    case 72: return launch_attn_t<T, 72>(qkv, out, rows, Tn, H, st);
-    case 128: return launch_attn_t<T, 128>(qkv, out, rows, Tn, H, st);
+    case 16: return launch_attn_t<T, 16>(qkv, out, ldo, rows, Tn, H, st);
+    case 32: return launch_attn_t<T, 32>(qkv, out, ldo, rows, Tn, H, st);
+    case 64: return launch_attn_t<T, 64>(qkv, out, ldo, rows, Tn, H, st);
+    case 72: return launch_attn_t<T, 72>(qkv, out, ldo, rows, Tn, H, st);
+    case 128: return launch_attn_t<T, 128>(qkv, out, ldo, rows, Tn, H, st);
   }
   SPECA_FAIL(SPECA_EUNSUPPORTED, "attention: head_dim %d (supported: 16, 32, 64, 72, 128)", hd);
 }
@@ -178,8 +178,8 @@ Error launch_gemm_simple(int dtype, const void* A, int64_t lda, const void* W, i
                              : launch_simple_t<float>(A, lda, W, ldw, M, N, K, epi, st);
 }
 
-Error launch_attention_simple(int dtype, const void* qkv, void* out, int rows, int T, int H, int hd, hipStream_t st) {
-  return dtype == SPECA_BF16 ? launch_attn_hd<bf16_t>(qkv, out, rows, T, H, hd, st) : launch_attn_hd<float>(qkv, out, rows, T, H, hd, st);
+Error launch_attention_simple(int dtype, const void* qkv, void* out, int64_t ldo, int rows, int T, int H, int hd, hipStream_t st) {
+  return dtype == SPECA_BF16 ? launch_attn_hd<bf16_t>(qkv, out, ldo, rows, T, H, hd, st) : launch_attn_hd<float>(qkv, out, ldo, rows, T, H, hd, st);
 }
 
 }  // namespace speca

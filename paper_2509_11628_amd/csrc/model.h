@@ -28,6 +28,7 @@ struct Model {
 
 // Factories; return nullptr + error on failure.
 Error make_dit_model(const speca_model_desc& d, const speca_weights* w, std::unique_ptr<Model>* out);
+Error make_mmdit_model(const speca_model_desc& d, const speca_weights* w, std::unique_ptr<Model>* out);
 
 // Solver update on device (DDIM eta=0 or flow Euler) with optional guidance combine.
 // latents [batch][n] fp32; model_out [rows][n] fp32, rows = batch or 2*batch.
