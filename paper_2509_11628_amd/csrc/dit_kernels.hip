@@ -39,32 +39,43 @@ __global__ void cond_sum_kernel(const float* __restrict__ temb, const T* __restr
   stf(sc + idx, c / (1.0f + expf(-c)));
 }
 
-// h[i][t][d] = sum_k patch(x_row)[t][k] Wp[d][k] + bp[d] + pos[t][d];  k = (c, pi, pj)
+// h[i][t][d] = sum_k patch(x_row)[t][k] Wp[d][k] + bp[d] + pos[t][d];  k = (c, pi, pj).
+// One thread per (token, 4 consecutive d): the patch values are read once per 4 outputs and are
+// wave-uniform loads when D >= 256; the result is stored as one float4.
 template <typename T>
-__global__ void patch_embed_kernel(const float* __restrict__ x, RowLabels xrow, const T* __restrict__ Wp, const T* __restrict__ bp,
-                                   const T* __restrict__ pos, float* __restrict__ h, int n, int C, int Hh, int Ww, int p, int D) {
+__global__ __launch_bounds__(256) void patch_embed_kernel(const float* __restrict__ x, RowLabels xrow, const T* __restrict__ Wp,
+                                                          const T* __restrict__ bp, const T* __restrict__ pos, float* __restrict__ h,
+                                                          int n, int C, int Hh, int Ww, int p, int D) {
   const int gw = Ww / p, gh = Hh / p;
   const int Tn = gh * gw;
+  const int dq = D >> 2;
   const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (idx >= static_cast<int64_t>(n) * Tn * D) return;
-  const int d = static_cast<int>(idx % D);
-  const int t = static_cast<int>((idx / D) % Tn);
-  const int i = static_cast<int>(idx / (static_cast<int64_t>(D) * Tn));
+  if (idx >= static_cast<int64_t>(n) * Tn * dq) return;
+  const int d = static_cast<int>(idx % dq) * 4;
+  const int t = static_cast<int>((idx / dq) % Tn);
+  const int i = static_cast<int>(idx / (static_cast<int64_t>(dq) * Tn));
   const int ti = t / gw, tj = t - ti * gw;
-  const float* xr = x + static_cast<int64_t>(xrow.v[i]) * C * Hh * Ww;
+  const float* xr = x + static_cast<int64_t>(xrow.v[i]) * C * Hh * Ww + (static_cast<int64_t>(ti) * p) * Ww + tj * p;
   const int Kp = C * p * p;
-  float acc = 0.0f;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  int k = 0;
   for (int c = 0; c < C; ++c)
     for (int pi = 0; pi < p; ++pi)
-      for (int pj = 0; pj < p; ++pj)
-        acc = fmaf(xr[(static_cast<int64_t>(c) * Hh + ti * p + pi) * Ww + tj * p + pj],
-                   ldf(Wp + static_cast<int64_t>(d) * Kp + (c * p + pi) * p + pj), acc);
-  h[idx] = acc + ldf(bp + d) + ldf(pos + static_cast<int64_t>(t) * D + d);
+      for (int pj = 0; pj < p; ++pj, ++k) {
+        const float xv = xr[(static_cast<int64_t>(c) * Hh + pi) * Ww + pj];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[q] = fmaf(xv, ldf(Wp + static_cast<int64_t>(d + q) * Kp + k), acc[q]);
+      }
+  float r[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) r[q] = acc[q] + ldf(bp + d + q) + ldf(pos + static_cast<int64_t>(t) * D + d + q);
+  *reinterpret_cast<float4*>(h + (static_cast<int64_t>(i) * Tn + t) * D + d) = make_float4(r[0], r[1], r[2], r[3]);
 }
 
 // One wave per token: y = LN(h) * (1 + scale[row]) + shift[row], LN without affine, eps 1e-6.
-// Statistics in fp32, two passes over registers.
-template <typename T, int PER_LANE>
+// Statistics in fp32, two passes over registers.  Each lane owns quads of four consecutive
+// channels (16-byte loads of h, shift and scale, 8- or 16-byte stores of y).
+template <typename T, int QUADS>
 __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restrict__ h, const float* __restrict__ shift,
                                                           const float* __restrict__ scale, const float* __restrict__ shift2,
                                                           const float* __restrict__ scale2, int split_tok, int64_t mod_stride,
@@ -75,34 +86,49 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
   const int i = static_cast<int>(tok / tokens_per_row);
   const bool second = static_cast<int>(tok - static_cast<int64_t>(i) * tokens_per_row) >= split_tok;   // tokens from split_tok on use the second set
   const float* hp = h + tok * D;
-  float v[PER_LANE];
+  const int nq = D >> 2;
+  float4 v[QUADS];
   float s = 0.0f;
 #pragma unroll
-  for (int j = 0; j < PER_LANE; ++j) {
-    const int d = lane + j * 64;
-    v[j] = d < D ? hp[d] : 0.0f;
-    s += v[j];
+  for (int j = 0; j < QUADS; ++j) {
+    const int q = lane + j * 64;
+    v[j] = q < nq ? *reinterpret_cast<const float4*>(hp + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+    s += (v[j].x + v[j].y) + (v[j].z + v[j].w);
   }
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
   const float mu = s / static_cast<float>(D);
-  float q = 0.0f;
+  float qs = 0.0f;
 #pragma unroll
-  for (int j = 0; j < PER_LANE; ++j) {
-    const int d = lane + j * 64;
-    const float c = d < D ? v[j] - mu : 0.0f;
-    q = fmaf(c, c, q);
+  for (int j = 0; j < QUADS; ++j) {
+    const int q = lane + j * 64;
+    if (q < nq) {
+      const float a = v[j].x - mu, b = v[j].y - mu, c = v[j].z - mu, d = v[j].w - mu;
+      qs += (a * a + b * b) + (c * c + d * d);
+    }
   }
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) q += __shfl_xor(q, off, 64);
-  const float rstd = rsqrtf(q / static_cast<float>(D) + 1e-6f);
+  for (int off = 32; off >= 1; off >>= 1) qs += __shfl_xor(qs, off, 64);
+  const float rstd = rsqrtf(qs / static_cast<float>(D) + 1e-6f);
   const float* sh = (second ? shift2 : shift) + static_cast<int64_t>(i) * mod_stride;
   const float* sc = (second ? scale2 : scale) + static_cast<int64_t>(i) * mod_stride;
   T* yp = y + tok * D;
 #pragma unroll
-  for (int j = 0; j < PER_LANE; ++j) {
-    const int d = lane + j * 64;
-    if (d < D) stf(yp + d, (v[j] - mu) * rstd * (1.0f + sc[d]) + sh[d]);
+  for (int j = 0; j < QUADS; ++j) {
+    const int q = lane + j * 64;
+    if (q < nq) {
+      const float4 a = *reinterpret_cast<const float4*>(sh + 4 * q), b = *reinterpret_cast<const float4*>(sc + 4 * q);
+      const float r0 = (v[j].x - mu) * rstd * (1.0f + b.x) + a.x, r1 = (v[j].y - mu) * rstd * (1.0f + b.y) + a.y;
+      const float r2 = (v[j].z - mu) * rstd * (1.0f + b.z) + a.z, r3 = (v[j].w - mu) * rstd * (1.0f + b.w) + a.w;
+      if (sizeof(T) == 2) {
+        uint2 o;
+        o.x = static_cast<uint32_t>(f32_to_bf16(r0)) | (static_cast<uint32_t>(f32_to_bf16(r1)) << 16);
+        o.y = static_cast<uint32_t>(f32_to_bf16(r2)) | (static_cast<uint32_t>(f32_to_bf16(r3)) << 16);
+        *reinterpret_cast<uint2*>(yp + 4 * q) = o;
+      } else {
+        *reinterpret_cast<float4*>(yp + 4 * q) = make_float4(r0, r1, r2, r3);
+      }
+    }
   }
 }
 
@@ -115,7 +141,7 @@ __global__ __launch_bounds__(256) void forecast_fold_kernel(CacheGeom g, RowTabl
                                                             float* __restrict__ h_out, const float* __restrict__ mod,
                                                             int64_t mod_stride, const int32_t* __restrict__ gate_off, int64_t split_elem,
                                                             int s0, int s1, int D) {
-  constexpr int V = 4;     // 4 elements per thread: 16 B of fp32 hidden, 8 B (bf16) or 16 B (fp32) of cache
+  constexpr int V = 8;     // 8 elements per thread: 2 x 16 B of fp32 hidden, 16 B (bf16) or 2 x 16 B (fp32) of every cached tensor
   const int i = blockIdx.y;
   const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * V;
   if (e >= g.E) return;
@@ -126,33 +152,41 @@ __global__ __launch_bounds__(256) void forecast_fold_kernel(CacheGeom g, RowTabl
 #pragma unroll
   for (int o = 0; o < NT; ++o) c[o] = o <= order ? rt.w[i][o] : 0.0f;
   const T* base = static_cast<const T*>(g.base);
-  const float4 hv = *reinterpret_cast<const float4*>(h_in + static_cast<int64_t>(i) * g.E + e);
-  float acc[V] = {hv.x, hv.y, hv.z, hv.w};
+  const float* hp = h_in + static_cast<int64_t>(i) * g.E + e;
+  const float4 h0 = *reinterpret_cast<const float4*>(hp), h1 = *reinterpret_cast<const float4*>(hp + 4);
+  float acc[V] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
   const float* mrow = mod + static_cast<int64_t>(i) * mod_stride + d;
+  const int sel = e >= split_elem ? 1 : 0;
   for (int slot = s0; slot < s1; ++slot) {
-    const float4 gv = *reinterpret_cast<const float4*>(mrow + gate_off[2 * slot + (e >= split_elem ? 1 : 0)]);
-    const float gg[V] = {gv.x, gv.y, gv.z, gv.w};
-    float f[V] = {0.0f, 0.0f, 0.0f, 0.0f};
+    const float* gp = mrow + gate_off[2 * slot + sel];
+    const float4 g0 = *reinterpret_cast<const float4*>(gp), g1 = *reinterpret_cast<const float4*>(gp + 4);
+    const float gg[V] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+    float f[V];
+#pragma unroll
+    for (int q = 0; q < V; ++q) f[q] = 0.0f;
 #pragma unroll
     for (int o = 0; o < NT; ++o)
       if (o <= order) {
-        float t4[V];
+        float t8[V];
         const T* p = base + g.offset(slot, o, row) + e;
         if (sizeof(T) == 2) {
-          const uint2 r = *reinterpret_cast<const uint2*>(p);
-          t4[0] = __uint_as_float(r.x << 16); t4[1] = __uint_as_float(r.x & 0xFFFF0000u);
-          t4[2] = __uint_as_float(r.y << 16); t4[3] = __uint_as_float(r.y & 0xFFFF0000u);
+          const uint4 r = *reinterpret_cast<const uint4*>(p);
+          const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q) { t8[2 * q] = __uint_as_float(w[q] << 16); t8[2 * q + 1] = __uint_as_float(w[q] & 0xFFFF0000u); }
         } else {
-          const float4 r = *reinterpret_cast<const float4*>(p);
-          t4[0] = r.x; t4[1] = r.y; t4[2] = r.z; t4[3] = r.w;
+          const float4 r0 = *reinterpret_cast<const float4*>(p), r1 = *reinterpret_cast<const float4*>(p + 4);
+          t8[0] = r0.x; t8[1] = r0.y; t8[2] = r0.z; t8[3] = r0.w; t8[4] = r1.x; t8[5] = r1.y; t8[6] = r1.z; t8[7] = r1.w;
         }
 #pragma unroll
-        for (int q = 0; q < V; ++q) f[q] = fmaf(c[o], t4[q], f[q]);
+        for (int q = 0; q < V; ++q) f[q] = fmaf(c[o], t8[q], f[q]);
       }
 #pragma unroll
     for (int q = 0; q < V; ++q) acc[q] = fmaf(gg[q], f[q], acc[q]);
   }
-  *reinterpret_cast<float4*>(h_out + static_cast<int64_t>(i) * g.E + e) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+  float* op = h_out + static_cast<int64_t>(i) * g.E + e;
+  *reinterpret_cast<float4*>(op) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+  *reinterpret_cast<float4*>(op + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
 }
 
 // model_out[row][c][i*p+pi][j*p+pj] = tok[i_compact][t=(i,j)][(c,pi,pj)]
@@ -196,7 +230,8 @@ Error launch_cond_sum(int dtype, const float* temb, const void* y_table, const R
 
 Error launch_patch_embed(int dtype, const float* x, const RowLabels& xrow, const void* Wp, const void* bp, const void* pos, float* h,
                          int n, int C, int Hh, int Ww, int p, int D, hipStream_t st) {
-  const int64_t total = static_cast<int64_t>(n) * (Hh / p) * (Ww / p) * D;
+  if (D % 4) SPECA_FAIL(SPECA_EUNSUPPORTED, "patch embed: hidden %d is not a multiple of 4", D);
+  const int64_t total = static_cast<int64_t>(n) * (Hh / p) * (Ww / p) * (D / 4);
   if (dtype == SPECA_BF16)
     patch_embed_kernel<bf16_t><<<blocks_for(total, 256), 256, 0, st>>>(x, xrow, static_cast<const bf16_t*>(Wp), static_cast<const bf16_t*>(bp), static_cast<const bf16_t*>(pos), h, n, C, Hh, Ww, p, D);
   else
@@ -210,11 +245,12 @@ static Error ln_mod_t(const float* h, const float* shift, const float* scale, co
                       int64_t mod_stride, void* y, int64_t n_tokens, int tokens_per_row, int D, hipStream_t st) {
   const unsigned grid = blocks_for(n_tokens, 4);
   T* yp = static_cast<T*>(y);
-  const int per = (D + 63) / 64;
+  if (D % 4) SPECA_FAIL(SPECA_EUNSUPPORTED, "LayerNorm: hidden %d is not a multiple of 4", D);
+  const int per = (D / 4 + 63) / 64;          // quads per lane
   if (per <= 1) ln_modulate_kernel<T, 1><<<grid, 256, 0, st>>>(h, shift, scale, shift2, scale2, split_tok, mod_stride, yp, n_tokens, tokens_per_row, D);
-  else if (per <= 4) ln_modulate_kernel<T, 4><<<grid, 256, 0, st>>>(h, shift, scale, shift2, scale2, split_tok, mod_stride, yp, n_tokens, tokens_per_row, D);
-  else if (per <= 18) ln_modulate_kernel<T, 18><<<grid, 256, 0, st>>>(h, shift, scale, shift2, scale2, split_tok, mod_stride, yp, n_tokens, tokens_per_row, D);
-  else if (per <= 48) ln_modulate_kernel<T, 48><<<grid, 256, 0, st>>>(h, shift, scale, shift2, scale2, split_tok, mod_stride, yp, n_tokens, tokens_per_row, D);
+  else if (per <= 2) ln_modulate_kernel<T, 2><<<grid, 256, 0, st>>>(h, shift, scale, shift2, scale2, split_tok, mod_stride, yp, n_tokens, tokens_per_row, D);
+  else if (per <= 5) ln_modulate_kernel<T, 5><<<grid, 256, 0, st>>>(h, shift, scale, shift2, scale2, split_tok, mod_stride, yp, n_tokens, tokens_per_row, D);
+  else if (per <= 12) ln_modulate_kernel<T, 12><<<grid, 256, 0, st>>>(h, shift, scale, shift2, scale2, split_tok, mod_stride, yp, n_tokens, tokens_per_row, D);
   else SPECA_FAIL(SPECA_EUNSUPPORTED, "LayerNorm: hidden %d > 3072", D);
   SPECA_HIP(hipGetLastError());
   return ok();
@@ -236,7 +272,7 @@ static Error fold_t(const CacheGeom& g, const RowTable& rt, const float* h_in, f
                     const int32_t* gate_off, int64_t split_elem, int s0, int s1, int D, hipStream_t st) {
   int mo = 0;
   for (int i = 0; i < rt.n; ++i) mo = rt.order[i] > mo ? rt.order[i] : mo;
-  dim3 grid(blocks_for(g.E, 256 * 4), rt.n);
+  dim3 grid(blocks_for(g.E, 256 * 8), rt.n);
   switch (mo) {
     case 0: forecast_fold_kernel<T, 1><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, split_elem, s0, s1, D); break;
     case 1: forecast_fold_kernel<T, 2><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, split_elem, s0, s1, D); break;
@@ -251,9 +287,9 @@ static Error fold_t(const CacheGeom& g, const RowTable& rt, const float* h_in, f
 Error launch_forecast_fold(const CacheGeom& g, const RowTable& rt, const float* h_in, float* h_out, const float* mod,
                            int64_t mod_stride, const int32_t* gate_off_dev, int64_t split_elem, int s0, int s1, int D, hipStream_t st) {
   if (rt.n <= 0 || rt.n > kMaxRows) SPECA_FAIL(SPECA_EINVAL, "forecast_fold: %d rows", rt.n);
-  if (g.E % 4 || D % 4) SPECA_FAIL(SPECA_EUNSUPPORTED, "forecast_fold needs hidden %% 4 == 0");
+  if (g.E % 8 || D % 8) SPECA_FAIL(SPECA_EUNSUPPORTED, "forecast_fold needs hidden %% 8 == 0");
   if (s0 < 0 || s1 > g.n_slots || s0 > s1) SPECA_FAIL(SPECA_EINVAL, "forecast_fold: slots [%d,%d)", s0, s1);
-  if (split_elem < 0 || split_elem % 4) SPECA_FAIL(SPECA_EINVAL, "forecast_fold: split");
+  if (split_elem < 0 || split_elem % 8) SPECA_FAIL(SPECA_EINVAL, "forecast_fold: split");
   return g.dtype == SPECA_BF16 ? fold_t<bf16_t>(g, rt, h_in, h_out, mod, mod_stride, gate_off_dev, split_elem, s0, s1, D, st)
                                : fold_t<float>(g, rt, h_in, h_out, mod, mod_stride, gate_off_dev, split_elem, s0, s1, D, st);
 }

@@ -16,6 +16,7 @@
 #include "dit_kernels.h"
 #include "gemm.h"
 #include "kernels.h"
+#include "mmdit_kernels.h"
 #include "model.h"
 
 namespace speca {
@@ -40,13 +41,19 @@ struct DiT final : Model {
   void* mod_b = nullptr;
   int64_t mod_n = 0;                 // L*6D + 2D
   int32_t* gate_off_dev = nullptr;   // [2L][2] offset of each slot's gate inside a modulation row
+  // trajectory-level modulation [S][batch_rows][mod_n] (see begin_trajectory)
+  float* traj_mod = nullptr;
+  void* traj_sc = nullptr;
+  size_t traj_cap = 0;
+  int traj_S = 0, traj_rows = 0;
+  bool traj_on = false;
   // workspace for up to cap_rows rows
   int cap_rows = 0;
   void *emb = nullptr, *t_hid = nullptr, *sc = nullptr, *xn = nullptr, *qkv = nullptr, *att = nullptr, *f1 = nullptr;
   float *temb = nullptr, *mod = nullptr, *h = nullptr, *h2 = nullptr, *feat = nullptr, *tok = nullptr;
 
   ~DiT() override {
-    for (void* p : {mod_w, mod_b, static_cast<void*>(gate_off_dev)})
+    for (void* p : {mod_w, mod_b, static_cast<void*>(gate_off_dev), static_cast<void*>(traj_mod), traj_sc})
       if (p) (void)hipFree(p);
     free_ws();
   }
@@ -87,10 +94,8 @@ struct DiT final : Model {
     return ok();
   }
 
-  // conditioning + modulation of all blocks for compact rows 0..n-1 (labels of rows[i])
-  Error conditioning(speca_ctx* ctx, float t, const int32_t* labels_per_row, const int32_t* rows, int n) {
-    hipStream_t st = ctx->stream;
-    ProfScope ps(ctx, SPECA_PROF_OTHER, 2.0 * n * D * (d.freq_dim + D + static_cast<double>(mod_n)), static_cast<double>(mod_n) * D * esz);
+  // SiLU(c) of compact rows 0..n-1 (labels of rows[i]) at timestep t, into sc_out [n][D]
+  Error cond_vector(hipStream_t st, float t, const int32_t* labels_per_row, const int32_t* rows, int n, void* sc_out) {
     RowLabels lab{};
     for (int i = 0; i < n; ++i) lab.v[i] = labels_per_row[rows[i]];
     SPECA_TRY(launch_sinusoid(d.dtype, emb, n, d.freq_dim, t, st));
@@ -100,12 +105,60 @@ struct DiT final : Model {
     GemmEpi e2;
     e2.mode = EPI_F32; e2.bias = t_b2; e2.out = temb; e2.ldo = D;
     SPECA_TRY(launch_gemm(d.dtype, t_hid, D, t_w2, D, n, D, D, e2, st));
-    SPECA_TRY(launch_cond_sum(d.dtype, temb, y_table, lab, n, D, sc, st));
+    return launch_cond_sum(d.dtype, temb, y_table, lab, n, D, sc_out, st);
+  }
+
+  // conditioning + modulation of all blocks for compact rows 0..n-1 at sampling step `step`
+  Error conditioning(speca_ctx* ctx, float t, const int32_t* labels_per_row, int step, const int32_t* rows, int n) {
+    hipStream_t st = ctx->stream;
+    if (traj_on && step >= 0 && step < traj_S) {
+      // inside a trajectory the modulation of this step was computed up front: pick the rows
+      ProfScope ps(ctx, SPECA_PROF_OTHER, 0.0, 2.0 * n * mod_n * 4);
+      RowLabels idx{};
+      for (int i = 0; i < n; ++i) idx.v[i] = rows[i];
+      return launch_gather_rows(SPECA_F32, traj_mod + static_cast<int64_t>(step) * traj_rows * mod_n, idx, mod, n, mod_n, st);
+    }
+    ProfScope ps(ctx, SPECA_PROF_OTHER, 2.0 * n * D * (d.freq_dim + D + static_cast<double>(mod_n)), static_cast<double>(mod_n) * D * esz);
+    SPECA_TRY(cond_vector(st, t, labels_per_row, rows, n, sc));
     GemmEpi e3;
     e3.mode = EPI_F32; e3.bias = mod_b; e3.out = mod; e3.ldo = mod_n;
     SPECA_TRY(launch_gemm(d.dtype, sc, D, mod_w, D, n, static_cast<int>(mod_n), D, e3, st));
     return ok();
   }
+
+  Error begin_trajectory(speca_ctx* ctx, const speca_cond*, const int32_t* labels_per_row, const float* timesteps, int S) override {
+    hipStream_t st = ctx->stream;
+    const int R = ctx->batch_rows;
+    const size_t total = static_cast<size_t>(S) * R;
+    if (total * mod_n * 4 > (static_cast<size_t>(8) << 30)) return ok();      // too large to be worth holding: per-step path
+    if (total > traj_cap) {
+      SPECA_HIP(hipStreamSynchronize(st));
+      if (traj_mod) (void)hipFree(traj_mod);
+      if (traj_sc) (void)hipFree(traj_sc);
+      traj_mod = nullptr; traj_sc = nullptr; traj_cap = 0;
+      if (hipMalloc(reinterpret_cast<void**>(&traj_mod), total * mod_n * 4) != hipSuccess || hipMalloc(&traj_sc, total * D * esz) != hipSuccess) {
+        (void)hipGetLastError();
+        if (traj_mod) (void)hipFree(traj_mod);
+        traj_mod = nullptr;
+        return ok();                                                          // no room: per-step path
+      }
+      traj_cap = total;
+    }
+    ProfScope ps(ctx, SPECA_PROF_OTHER, 2.0 * total * D * static_cast<double>(mod_n), static_cast<double>(mod_n) * D * esz + total * mod_n * 4.0);
+    std::vector<int32_t> rows(cap_rows);
+    for (int s = 0; s < S; ++s)
+      for (int r0 = 0; r0 < R; r0 += cap_rows) {
+        const int n = std::min(cap_rows, R - r0);
+        for (int i = 0; i < n; ++i) rows[i] = r0 + i;
+        SPECA_TRY(cond_vector(st, timesteps[s], labels_per_row, rows.data(), n, static_cast<char*>(traj_sc) + (static_cast<size_t>(s) * R + r0) * D * esz));
+      }
+    GemmEpi e;
+    e.mode = EPI_F32; e.bias = mod_b; e.out = traj_mod; e.ldo = mod_n;
+    SPECA_TRY(launch_gemm(d.dtype, traj_sc, D, mod_w, D, static_cast<int>(total), static_cast<int>(mod_n), D, e, st));
+    traj_S = S; traj_rows = R; traj_on = true;
+    return ok();
+  }
+  void end_trajectory() override { traj_on = false; }
 
   Error embed(speca_ctx* ctx, const float* x, int x_mod, const int32_t* rows, int n) {
     hipStream_t st = ctx->stream;
@@ -191,7 +244,7 @@ struct DiT final : Model {
     if (n > cap_rows) SPECA_FAIL(SPECA_EUNSUPPORTED, "at most %d rows per launch", cap_rows);
     RowTable rt;
     SPECA_TRY(build_refresh_table(ctx, step, rows, n, &rt));
-    SPECA_TRY(conditioning(ctx, cond->timestep, labels_per_row, rows, n));
+    SPECA_TRY(conditioning(ctx, cond->timestep, labels_per_row, step, rows, n));
     SPECA_TRY(embed(ctx, x, x_mod, rows, n));
     for (int l = 0; l < L; ++l) {
       SPECA_TRY(attn_branch(ctx, l, h, n, &rt));
@@ -221,7 +274,7 @@ struct DiT final : Model {
       }
     }
     const int lv = ctx->cfg.verify_block >= 0 ? ctx->cfg.verify_block : L - 1;
-    SPECA_TRY(conditioning(ctx, cond->timestep, labels_per_row, rows, n));
+    SPECA_TRY(conditioning(ctx, cond->timestep, labels_per_row, step, rows, n));
     SPECA_TRY(embed(ctx, x, x_mod, rows, n));
     // Eq. 2 for every slot before the verify block, folded into h
     const double tens = table_tensors(rt), Ed = static_cast<double>(ctx->geom.E);

@@ -48,13 +48,18 @@ struct MMDiT final : Model {
   int64_t mod_n = 0, base_s = 0, base_f = 0;
   int32_t* gate_off_dev = nullptr;    // [n_slots][2]
   std::vector<int> first_slot;        // per block, plus end
+  float* traj_mod = nullptr;          // [S][batch_rows][mod_n], see begin_trajectory
+  void* traj_sc = nullptr;
+  size_t traj_cap = 0;
+  int traj_S = 0, traj_rows = 0;
+  bool traj_on = false;
   int cap_rows = 0;
   void *emb = nullptr, *t_hid = nullptr, *v_in = nullptr, *v_hid = nullptr, *sc = nullptr, *patches = nullptr, *xn = nullptr, *qkv = nullptr,
        *att = nullptr, *f1 = nullptr, *cat = nullptr;
   float *temb = nullptr, *vemb = nullptr, *mod = nullptr, *h = nullptr, *h2 = nullptr, *feat = nullptr, *tok = nullptr;
 
   ~MMDiT() override {
-    for (void* p : {mod_w, mod_b, static_cast<void*>(gate_off_dev)})
+    for (void* p : {mod_w, mod_b, static_cast<void*>(gate_off_dev), static_cast<void*>(traj_mod), traj_sc})
       if (p) (void)hipFree(p);
     free_ws();
   }
@@ -99,27 +104,74 @@ struct MMDiT final : Model {
     return launch_gemm(d.dtype, A, lda, W, ldw, static_cast<int>(M), N, K, e, ctx->stream);
   }
 
-  Error conditioning(speca_ctx* ctx, const speca_cond* cond, const int32_t* rows, int n) {
+  // SiLU(vec) of compact rows 0..n-1 at timestep t, into sc_out [n][D]
+  Error cond_vector(speca_ctx* ctx, float t, const speca_cond* cond, const int32_t* rows, int n, void* sc_out) {
     hipStream_t st = ctx->stream;
     if (!cond->pooled) SPECA_FAIL(SPECA_EINVAL, "cond->pooled is NULL");
-    SPECA_TRY(launch_sinusoid(d.dtype, emb, n, d.freq_dim, cond->timestep, st));
+    SPECA_TRY(launch_sinusoid(d.dtype, emb, n, d.freq_dim, t, st));
     GemmEpi e;
     e.mode = EPI_SILU; e.bias = t_b1; e.out = t_hid; e.ldo = D;
-    SPECA_TRY(gemm(ctx, SPECA_PROF_OTHER, emb, d.freq_dim, t_w1, d.freq_dim, n, D, d.freq_dim, e));
+    SPECA_TRY(launch_gemm(d.dtype, emb, d.freq_dim, t_w1, d.freq_dim, n, D, d.freq_dim, e, st));
     e = GemmEpi(); e.mode = EPI_F32; e.bias = t_b2; e.out = temb; e.ldo = D;
-    SPECA_TRY(gemm(ctx, SPECA_PROF_OTHER, t_hid, D, t_w2, D, n, D, D, e));
+    SPECA_TRY(launch_gemm(d.dtype, t_hid, D, t_w2, D, n, D, D, e, st));
     RowLabels idx{};
     for (int i = 0; i < n; ++i) idx.v[i] = rows[i];
     SPECA_TRY(launch_gather_rows(d.dtype, cond->pooled, idx, v_in, n, d.vec_dim, st));
     e = GemmEpi(); e.mode = EPI_SILU; e.bias = v_b1; e.out = v_hid; e.ldo = D;
-    SPECA_TRY(gemm(ctx, SPECA_PROF_OTHER, v_in, d.vec_dim, v_w1, d.vec_dim, n, D, d.vec_dim, e));
+    SPECA_TRY(launch_gemm(d.dtype, v_in, d.vec_dim, v_w1, d.vec_dim, n, D, d.vec_dim, e, st));
     e = GemmEpi(); e.mode = EPI_F32; e.bias = v_b2; e.out = vemb; e.ldo = D;
-    SPECA_TRY(gemm(ctx, SPECA_PROF_OTHER, v_hid, D, v_w2, D, n, D, D, e));
-    SPECA_TRY(launch_silu_sum(d.dtype, temb, vemb, sc, static_cast<int64_t>(n) * D, st));
-    e = GemmEpi(); e.mode = EPI_F32; e.bias = mod_b; e.out = mod; e.ldo = mod_n;
-    SPECA_TRY(gemm(ctx, SPECA_PROF_OTHER, sc, D, mod_w, D, n, static_cast<int>(mod_n), D, e));
+    SPECA_TRY(launch_gemm(d.dtype, v_hid, D, v_w2, D, n, D, D, e, st));
+    return launch_silu_sum(d.dtype, temb, vemb, sc_out, static_cast<int64_t>(n) * D, st);
+  }
+
+  Error conditioning(speca_ctx* ctx, const speca_cond* cond, int step, const int32_t* rows, int n) {
+    hipStream_t st = ctx->stream;
+    if (traj_on && step >= 0 && step < traj_S) {
+      ProfScope ps(ctx, SPECA_PROF_OTHER, 0.0, 2.0 * n * mod_n * 4);
+      RowLabels idx{};
+      for (int i = 0; i < n; ++i) idx.v[i] = rows[i];
+      return launch_gather_rows(SPECA_F32, traj_mod + static_cast<int64_t>(step) * traj_rows * mod_n, idx, mod, n, mod_n, st);
+    }
+    ProfScope ps(ctx, SPECA_PROF_OTHER, 2.0 * n * D * static_cast<double>(mod_n), static_cast<double>(mod_n) * D * esz);
+    SPECA_TRY(cond_vector(ctx, cond->timestep, cond, rows, n, sc));
+    GemmEpi e;
+    e.mode = EPI_F32; e.bias = mod_b; e.out = mod; e.ldo = mod_n;
+    return launch_gemm(d.dtype, sc, D, mod_w, D, n, static_cast<int>(mod_n), D, e, st);
+  }
+
+  Error begin_trajectory(speca_ctx* ctx, const speca_cond* cond, const int32_t*, const float* timesteps, int S) override {
+    hipStream_t st = ctx->stream;
+    const int R = ctx->batch_rows;
+    const size_t total = static_cast<size_t>(S) * R;
+    if (total * mod_n * 4 > (static_cast<size_t>(8) << 30)) return ok();      // too large to be worth holding: per-step path
+    if (total > traj_cap) {
+      SPECA_HIP(hipStreamSynchronize(st));
+      if (traj_mod) (void)hipFree(traj_mod);
+      if (traj_sc) (void)hipFree(traj_sc);
+      traj_mod = nullptr; traj_sc = nullptr; traj_cap = 0;
+      if (hipMalloc(reinterpret_cast<void**>(&traj_mod), total * mod_n * 4) != hipSuccess || hipMalloc(&traj_sc, total * D * esz) != hipSuccess) {
+        (void)hipGetLastError();
+        if (traj_mod) (void)hipFree(traj_mod);
+        traj_mod = nullptr;
+        return ok();
+      }
+      traj_cap = total;
+    }
+    ProfScope ps(ctx, SPECA_PROF_OTHER, 2.0 * total * D * static_cast<double>(mod_n), static_cast<double>(mod_n) * D * esz + total * mod_n * 4.0);
+    std::vector<int32_t> rows(cap_rows);
+    for (int s = 0; s < S; ++s)
+      for (int r0 = 0; r0 < R; r0 += cap_rows) {
+        const int n = std::min(cap_rows, R - r0);
+        for (int i = 0; i < n; ++i) rows[i] = r0 + i;
+        SPECA_TRY(cond_vector(ctx, timesteps[s], cond, rows.data(), n, static_cast<char*>(traj_sc) + (static_cast<size_t>(s) * R + r0) * D * esz));
+      }
+    GemmEpi e;
+    e.mode = EPI_F32; e.bias = mod_b; e.out = traj_mod; e.ldo = mod_n;
+    SPECA_TRY(launch_gemm(d.dtype, traj_sc, D, mod_w, D, static_cast<int>(total), static_cast<int>(mod_n), D, e, st));
+    traj_S = S; traj_rows = R; traj_on = true;
     return ok();
   }
+  void end_trajectory() override { traj_on = false; }
 
   Error embed(speca_ctx* ctx, const float* x, int x_mod, const speca_cond* cond, const int32_t* rows, int n) {
     hipStream_t st = ctx->stream;
@@ -265,8 +317,8 @@ struct MMDiT final : Model {
     return launch_unpatchify_video(tok, r, model_out, n, d.in_channels, d.latent_t, d.latent_h, d.latent_w, d.patch, st);
   }
 
-  Error begin(speca_ctx* ctx, const float* x, int x_mod, const speca_cond* cond, const int32_t* rows, int n) {
-    SPECA_TRY(conditioning(ctx, cond, rows, n));
+  Error begin(speca_ctx* ctx, const float* x, int x_mod, const speca_cond* cond, int step, const int32_t* rows, int n) {
+    SPECA_TRY(conditioning(ctx, cond, step, rows, n));
     return embed(ctx, x, x_mod, cond, rows, n);
   }
 
@@ -275,7 +327,7 @@ struct MMDiT final : Model {
     if (n > cap_rows) SPECA_FAIL(SPECA_EUNSUPPORTED, "at most %d rows per launch", cap_rows);
     RowTable rt;
     SPECA_TRY(build_refresh_table(ctx, step, rows, n, &rt));
-    SPECA_TRY(begin(ctx, x, x_mod, cond, rows, n));
+    SPECA_TRY(begin(ctx, x, x_mod, cond, step, rows, n));
     for (int b = 0; b < nd + ns; ++b) SPECA_TRY(block(ctx, b, h, n, &rt, nullptr));
     SPECA_TRY(final_layer(ctx, h, rows, n, model_out));
     push_refs(ctx, step, rows, n);
@@ -292,7 +344,7 @@ struct MMDiT final : Model {
     const int nb = nd + ns;
     const int lv = ctx->cfg.verify_block >= 0 ? ctx->cfg.verify_block : nb - 1;
     const int s_lv = first_slot[lv], s_end = first_slot[nb], v_slot = first_slot[lv + 1] - 1;
-    SPECA_TRY(begin(ctx, x, x_mod, cond, rows, n));
+    SPECA_TRY(begin(ctx, x, x_mod, cond, step, rows, n));
     const double tens = table_tensors(rt), Ed = static_cast<double>(ctx->geom.E);
     const int64_t split = static_cast<int64_t>(Tt) * D;
     {

@@ -24,6 +24,13 @@ struct Model {
   virtual Error spec_step(speca_ctx* ctx, const float* x, int x_mod, const speca_cond* cond, const int32_t* labels_per_row,
                           int step, const int32_t* rows, int n, const float* tau_per_row, int pair_stride,
                           float* model_out) = 0;
+  // Whole-trajectory preparation: the conditioning of every step is known up front (the solver
+  // tables are data), so the modulation of all steps and rows can be one large GEMM instead of a
+  // weight-bound skinny one per step.  Optional; steps outside a trajectory compute it themselves.
+  virtual Error begin_trajectory(speca_ctx*, const speca_cond*, const int32_t* /*labels_per_row*/, const float* /*timesteps*/, int /*S*/) {
+    return ok();
+  }
+  virtual void end_trajectory() {}
 };
 
 // Factories; return nullptr + error on failure.

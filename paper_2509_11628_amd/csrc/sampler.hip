@@ -95,6 +95,9 @@ Error sample_impl(speca_ctx* ctx, float* latents, int batch, const speca_cond* c
   const float nan = std::numeric_limits<float>::quiet_NaN();
   const int samples_per_launch = kMaxRows / R;
 
+  SPECA_TRY(ctx->model->begin_trajectory(ctx, cond, labels.data(), solver->timesteps, S));
+  struct TrajGuard { Model* m; ~TrajGuard() { m->end_trajectory(); } } traj_guard{ctx->model.get()};
+
   for (int s = 0; s < S; ++s) {
     speca_cond c = *cond;
     c.timestep = solver->timesteps[s];
