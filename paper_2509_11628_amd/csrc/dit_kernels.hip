@@ -58,14 +58,46 @@ __global__ __launch_bounds__(256) void patch_embed_kernel(const float* __restric
   const float* xr = x + static_cast<int64_t>(xrow.v[i]) * C * Hh * Ww + (static_cast<int64_t>(ti) * p) * Ww + tj * p;
   const int Kp = C * p * p;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  int k = 0;
-  for (int c = 0; c < C; ++c)
-    for (int pi = 0; pi < p; ++pi)
-      for (int pj = 0; pj < p; ++pj, ++k) {
-        const float xv = xr[(static_cast<int64_t>(c) * Hh + pi) * Ww + pj];
+  if (Kp == 16 && p == 2) {
+    // the common 2x2 x 4-channel patch: the 16 patch values in registers, weight rows as 16-/32-byte vectors
+    float xv[16];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) acc[q] = fmaf(xv, ldf(Wp + static_cast<int64_t>(d + q) * Kp + k), acc[q]);
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int pi = 0; pi < 2; ++pi) {
+        const float2 t2 = *reinterpret_cast<const float2*>(xr + (static_cast<int64_t>(c) * Hh + pi) * Ww);
+        xv[(c * 2 + pi) * 2] = t2.x;
+        xv[(c * 2 + pi) * 2 + 1] = t2.y;
       }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float w[16];
+      const T* wp = Wp + static_cast<int64_t>(d + q) * 16;
+      if (sizeof(T) == 2) {
+        const uint4 a = *reinterpret_cast<const uint4*>(wp), b = *reinterpret_cast<const uint4*>(wp + 8);
+        const uint32_t u[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { w[2 * j] = __uint_as_float(u[j] << 16); w[2 * j + 1] = __uint_as_float(u[j] & 0xFFFF0000u); }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float4 a = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(wp) + 4 * j);
+          w[4 * j] = a.x; w[4 * j + 1] = a.y; w[4 * j + 2] = a.z; w[4 * j + 3] = a.w;
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 16; ++k) acc[q] = fmaf(xv[k], w[k], acc[q]);
+    }
+  } else {
+    int k = 0;
+    for (int c = 0; c < C; ++c)
+      for (int pi = 0; pi < p; ++pi)
+        for (int pj = 0; pj < p; ++pj, ++k) {
+          const float xv = xr[(static_cast<int64_t>(c) * Hh + pi) * Ww + pj];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) acc[q] = fmaf(xv, ldf(Wp + static_cast<int64_t>(d + q) * Kp + k), acc[q]);
+        }
+  }
   float r[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q) r[q] = acc[q] + ldf(bp + d + q) + ldf(pos + static_cast<int64_t>(t) * D + d + q);

@@ -38,6 +38,9 @@ template <> struct Store4<bf16_t> {
   }
 };
 
+template <typename T, int MODE>
+__device__ inline void epilogue_apply(const GemmEpi& e, int m, int n, float v[4]);
+
 // T = model / cache storage type.  MODE is a compile-time EpiMode.
 template <typename T, int MODE>
 __device__ inline void epilogue_quad(const GemmEpi& e, int m, int n, float v[4]) {
@@ -47,6 +50,12 @@ __device__ inline void epilogue_quad(const GemmEpi& e, int m, int n, float v[4])
 #pragma unroll
     for (int i = 0; i < 4; ++i) v[i] += b[i];
   }
+  epilogue_apply<T, MODE>(e, m, n, v);
+}
+
+// The epilogue after the bias has been added.
+template <typename T, int MODE>
+__device__ inline void epilogue_apply(const GemmEpi& e, int m, int n, float v[4]) {
   if (MODE == EPI_STORE || MODE == EPI_GELU || MODE == EPI_SILU) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -88,6 +97,122 @@ __device__ inline void epilogue_quad(const GemmEpi& e, int m, int n, float v[4])
     for (int q = 0; q < 4; ++q) hv[q] = fmaf(g[q], v[q], hv[q]);
     Store4<float>::st(hp, hv);
   }
+}
+
+
+// ---- two-phase form of the branch epilogue --------------------------------------------------
+// The GEMM kernels apply the branch epilogue to several rows per thread.  Done row by row,
+// every row costs a full memory latency (load old differences / residual -> compute -> store).
+// Splitting it into a load phase and a finish phase lets a thread put the loads of a whole
+// batch of rows in flight before the first store.
+template <typename T>
+struct BranchRegs {
+  float old[SPECA_MAX_ORDER][4];   // D^0 .. D^{order-1} before the refresh
+  float g[4], hv[4];
+};
+
+template <typename T>
+__device__ inline void branch_load(const GemmEpi& e, int m, int n, BranchRegs<T>& r) {
+  const int i = m / e.tokens;
+  const int t = m - i * e.tokens;
+  if (e.refresh) {
+    const int order = e.rt.order[i];
+    const int64_t pos = e.cache_elem_offset + static_cast<int64_t>(t) * e.ldh + n;
+    const T* base = static_cast<const T*>(e.g.base);
+#pragma unroll
+    for (int o = 0; o < SPECA_MAX_ORDER; ++o)
+      if (o < order) Store4<T>::ld(base + e.g.offset(e.slot, o, e.rt.row[i]) + pos, r.old[o]);
+  }
+  Store4<float>::ld(e.gate + static_cast<int64_t>(i) * e.gate_stride + n, r.g);
+  Store4<float>::ld(e.h + static_cast<int64_t>(m) * e.ldh + n, r.hv);
+}
+
+// v = accumulators + bias (already added by the caller)
+template <typename T>
+__device__ inline void branch_finish(const GemmEpi& e, int m, int n, const float v[4], BranchRegs<T>& r) {
+  const int i = m / e.tokens;
+  const int t = m - i * e.tokens;
+  if (e.refresh) {
+    const int order = e.rt.order[i];
+    const int64_t pos = e.cache_elem_offset + static_cast<int64_t>(t) * e.ldh + n;
+    T* base = static_cast<T*>(e.g.base);
+    float cur[4] = {v[0], v[1], v[2], v[3]};
+    Store4<T>::st(base + e.g.offset(e.slot, 0, e.rt.row[i]) + pos, cur);
+#pragma unroll
+    for (int o = 1; o <= SPECA_MAX_ORDER; ++o)
+      if (o <= order) {
+        const float inv = e.rt.w[i][o - 1];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) cur[q] = (cur[q] - r.old[o - 1][q]) * inv;
+        Store4<T>::st(base + e.g.offset(e.slot, o, e.rt.row[i]) + pos, cur);
+      }
+  }
+  float hv[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) hv[q] = fmaf(r.g[q], v[q], r.hv[q]);
+  Store4<float>::st(e.h + static_cast<int64_t>(m) * e.ldh + n, hv);
+}
+
+
+// ---- block-uniform form ------------------------------------------------------------------------
+// When all rows of a tile belong to one batch row, the row table lookup (cache row, order,
+// reciprocal divisors) is the same for the whole block: it is read once through scalar loads and
+// the per-quad work needs no table access in front of its cache loads.
+template <typename T>
+struct BranchRow {
+  int order;                         // differences to refresh (0 when refresh is off)
+  bool refresh;
+  float inv[SPECA_MAX_ORDER];
+  T* d[SPECA_MAX_ORDER + 1];         // D^o of (slot, cache row), already offset by cache_elem_offset
+  const float* gate;
+  int t0;                            // token index of tile row 0 inside the batch row
+};
+
+template <typename T>
+__device__ inline BranchRow<T> branch_row(const GemmEpi& e, int i, int m0) {
+  BranchRow<T> b;
+  b.refresh = e.refresh != 0;
+  b.order = b.refresh ? e.rt.order[i] : 0;
+  T* base = static_cast<T*>(e.g.base);
+#pragma unroll
+  for (int o = 0; o <= SPECA_MAX_ORDER; ++o)
+    b.d[o] = (b.refresh && o <= b.order) ? base + e.g.offset(e.slot, o, e.rt.row[i]) + e.cache_elem_offset : base;
+#pragma unroll
+  for (int o = 0; o < SPECA_MAX_ORDER; ++o) b.inv[o] = (b.refresh && o < b.order) ? e.rt.w[i][o] : 0.0f;
+  b.gate = e.gate + static_cast<int64_t>(i) * e.gate_stride;
+  b.t0 = m0 - i * e.tokens;
+  return b;
+}
+
+template <typename T>
+__device__ inline void branch_load_u(const GemmEpi& e, const BranchRow<T>& b, int r, int m, int n, BranchRegs<T>& regs) {
+  const int64_t pos = static_cast<int64_t>(b.t0 + r) * e.ldh + n;
+#pragma unroll
+  for (int o = 0; o < SPECA_MAX_ORDER; ++o)
+    if (o < b.order) Store4<T>::ld(b.d[o] + pos, regs.old[o]);
+  Store4<float>::ld(b.gate + n, regs.g);
+  Store4<float>::ld(e.h + static_cast<int64_t>(m) * e.ldh + n, regs.hv);
+}
+
+template <typename T>
+__device__ inline void branch_finish_u(const GemmEpi& e, const BranchRow<T>& b, int r, int m, int n, const float v[4], BranchRegs<T>& regs) {
+  if (b.refresh) {
+    const int64_t pos = static_cast<int64_t>(b.t0 + r) * e.ldh + n;
+    float cur[4] = {v[0], v[1], v[2], v[3]};
+    Store4<T>::st(b.d[0] + pos, cur);
+#pragma unroll
+    for (int o = 1; o <= SPECA_MAX_ORDER; ++o)
+      if (o <= b.order) {
+        const float inv = b.inv[o - 1];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) cur[q] = (cur[q] - regs.old[o - 1][q]) * inv;
+        Store4<T>::st(b.d[o] + pos, cur);
+      }
+  }
+  float hv[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) hv[q] = fmaf(regs.g[q], v[q], regs.hv[q]);
+  Store4<float>::st(e.h + static_cast<int64_t>(m) * e.ldh + n, hv);
 }
 
 }  // namespace speca

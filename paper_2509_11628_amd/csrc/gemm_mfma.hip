@@ -180,14 +180,66 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const uint16_t
   __syncthreads();
   constexpr int QPR = BN / 4;                        // quads per row
   constexpr int RPP = NT / QPR;                      // rows per pass
+  constexpr int PASSES = BM / RPP;
   const int qc = (tid % QPR) * 4, qr = tid / QPR;
+  const int n = n0 + qc;
+  if (n >= N) return;
+  float bias[4] = {0.f, 0.f, 0.f, 0.f};
+  if (epi.bias) Store4<bf16_t>::ld(static_cast<const bf16_t*>(epi.bias) + n, bias);
+  if (MODE == EPI_BRANCH) {
+    // batches of EB rows: all loads of the batch are issued before its first store
+    constexpr int EB = PASSES % 4 == 0 ? 4 : (PASSES % 2 == 0 ? 2 : 1);
+    const int m_last = (m0 + BM < M ? m0 + BM : M) - 1;
+    const int i_first = m0 / epi.tokens;
+    if (i_first == m_last / epi.tokens) {
+      // the whole tile lies inside one batch row: block-uniform row table, scalar loads
+      const BranchRow<bf16_t> br = branch_row<bf16_t>(epi, i_first, m0);
+      for (int p0 = 0; p0 < PASSES; p0 += EB) {
+        BranchRegs<bf16_t> regs[EB];
+#pragma unroll
+        for (int u = 0; u < EB; ++u) {
+          const int r = qr + (p0 + u) * RPP;
+          if (m0 + r < M) branch_load_u<bf16_t>(epi, br, r, m0 + r, n, regs[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < EB; ++u) {
+          const int r = qr + (p0 + u) * RPP;
+          if (m0 + r < M) {
+            const float4 t = *reinterpret_cast<const float4*>(Cs + r * CST + qc);
+            const float v[4] = {t.x + bias[0], t.y + bias[1], t.z + bias[2], t.w + bias[3]};
+            branch_finish_u<bf16_t>(epi, br, r, m0 + r, n, v, regs[u]);
+          }
+        }
+      }
+    } else {
+      for (int p0 = 0; p0 < PASSES; p0 += EB) {
+        BranchRegs<bf16_t> regs[EB];
+#pragma unroll
+        for (int u = 0; u < EB; ++u) {
+          const int m = m0 + qr + (p0 + u) * RPP;
+          if (m < M) branch_load<bf16_t>(epi, m, n, regs[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < EB; ++u) {
+          const int r = qr + (p0 + u) * RPP;
+          const int m = m0 + r;
+          if (m < M) {
+            const float4 t = *reinterpret_cast<const float4*>(Cs + r * CST + qc);
+            const float v[4] = {t.x + bias[0], t.y + bias[1], t.z + bias[2], t.w + bias[3]};
+            branch_finish<bf16_t>(epi, m, n, v, regs[u]);
+          }
+        }
+      }
+    }
+  } else {
 #pragma unroll 4
-  for (int r = qr; r < BM; r += RPP) {
-    const int m = m0 + r, n = n0 + qc;
-    if (m < M && n < N) {
-      const float4 t = *reinterpret_cast<const float4*>(Cs + r * CST + qc);
-      float v[4] = {t.x, t.y, t.z, t.w};
-      epilogue_quad<bf16_t, MODE>(epi, m, n, v);
+    for (int r = qr; r < BM; r += RPP) {
+      const int m = m0 + r;
+      if (m < M) {
+        const float4 t = *reinterpret_cast<const float4*>(Cs + r * CST + qc);
+        float v[4] = {t.x + bias[0], t.y + bias[1], t.z + bias[2], t.w + bias[3]};
+        epilogue_apply<bf16_t, MODE>(epi, m, n, v);
+      }
     }
   }
 }
