@@ -164,6 +164,8 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
   }
 }
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 // Speculative step: h_out[i][e] = h_in[i][e] + sum_{slot in [s0,s1)} gate_slot[i][d] * sum_o c[i][o] D^o[slot][row_i][e]
 // (Eq. 2 for every slot, folded into the residual stream; only the hidden state is written).
 // gate of slot j for compact row i: mod[i * mod_stride + gate_off[2j + s] + d], s = 0 for elements below
@@ -180,39 +182,46 @@ __global__ __launch_bounds__(256) void forecast_fold_kernel(CacheGeom g, RowTabl
   const int d = static_cast<int>(e % D);
   const int row = rt.row[i];
   const int order = rt.order[i];
+  // Orders above this row's available one get coefficient 0 and re-read the highest valid tensor
+  // (finite data), so the loads of a slot are unconditional and can all be in flight together.
   float c[NT];
+  int oc[NT];
 #pragma unroll
-  for (int o = 0; o < NT; ++o) c[o] = o <= order ? rt.w[i][o] : 0.0f;
+  for (int o = 0; o < NT; ++o) {
+    c[o] = o <= order ? rt.w[i][o] : 0.0f;
+    oc[o] = o <= order ? o : order;
+  }
   const T* base = static_cast<const T*>(g.base);
   const float* hp = h_in + static_cast<int64_t>(i) * g.E + e;
   const float4 h0 = *reinterpret_cast<const float4*>(hp), h1 = *reinterpret_cast<const float4*>(hp + 4);
   float acc[V] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
   const float* mrow = mod + static_cast<int64_t>(i) * mod_stride + d;
-  const int sel = e >= split_elem ? 1 : 0;
+  const bool sel = e >= split_elem;
+  // four slots per trip: 4 * NT cache loads in flight per lane (measured best among 1/2/4/8)
+#pragma unroll 4
   for (int slot = s0; slot < s1; ++slot) {
-    const float* gp = mrow + gate_off[2 * slot + sel];
+    const int off0 = gate_off[2 * slot], off1 = gate_off[2 * slot + 1];     // block-uniform: scalar loads
+    const float* gp = mrow + (sel ? off1 : off0);
     const float4 g0 = *reinterpret_cast<const float4*>(gp), g1 = *reinterpret_cast<const float4*>(gp + 4);
     const float gg[V] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
     float f[V];
 #pragma unroll
     for (int q = 0; q < V; ++q) f[q] = 0.0f;
 #pragma unroll
-    for (int o = 0; o < NT; ++o)
-      if (o <= order) {
-        float t8[V];
-        const T* p = base + g.offset(slot, o, row) + e;
-        if (sizeof(T) == 2) {
-          const uint4 r = *reinterpret_cast<const uint4*>(p);
-          const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+    for (int o = 0; o < NT; ++o) {
+      float t8[V];
+      const T* p = base + g.offset(slot, oc[o], row) + e;
+      if (sizeof(T) == 2) {
+        const u32x4 r = *reinterpret_cast<const u32x4*>(p);
 #pragma unroll
-          for (int q = 0; q < 4; ++q) { t8[2 * q] = __uint_as_float(w[q] << 16); t8[2 * q + 1] = __uint_as_float(w[q] & 0xFFFF0000u); }
-        } else {
-          const float4 r0 = *reinterpret_cast<const float4*>(p), r1 = *reinterpret_cast<const float4*>(p + 4);
-          t8[0] = r0.x; t8[1] = r0.y; t8[2] = r0.z; t8[3] = r0.w; t8[4] = r1.x; t8[5] = r1.y; t8[6] = r1.z; t8[7] = r1.w;
-        }
-#pragma unroll
-        for (int q = 0; q < V; ++q) f[q] = fmaf(c[o], t8[q], f[q]);
+        for (int q = 0; q < 4; ++q) { t8[2 * q] = __uint_as_float(r[q] << 16); t8[2 * q + 1] = __uint_as_float(r[q] & 0xFFFF0000u); }
+      } else {
+        const float4 r0 = *reinterpret_cast<const float4*>(p), r1 = *reinterpret_cast<const float4*>(p + 4);
+        t8[0] = r0.x; t8[1] = r0.y; t8[2] = r0.z; t8[3] = r0.w; t8[4] = r1.x; t8[5] = r1.y; t8[6] = r1.z; t8[7] = r1.w;
       }
+#pragma unroll
+      for (int q = 0; q < V; ++q) f[q] = fmaf(c[o], t8[q], f[q]);
+    }
 #pragma unroll
     for (int q = 0; q < V; ++q) acc[q] = fmaf(gg[q], f[q], acc[q]);
   }
