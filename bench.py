@@ -33,6 +33,16 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0         # MI355X HBM3E
 
 
+# L2 <-> fabric bytes per launch from rocprofv3 counter runs of these same workloads
+# (2 x FETCH_SIZE + WRITE_SIZE in bytes, the factor 2 from a plain copy of known size under the
+# same counters; launch-weighted over the kernels of the class).  Counters cannot be read from
+# inside the process, so the figures are carried here; profiles/hbm_counters.txt holds the runs.
+MEASURED_TRAFFIC = {
+    ("dit_xl2", "gemm"): 134.1e6,
+    ("forecast", "forecast"): 528.5e6,
+}
+
+
 def cpu_baseline(shape, weights, seconds_budget=30.0):
     """The oracle as it stands, on the host cores: one full-compute step of one guided
     sample (2 of the 16 rows), scaled to the 16-row batch step."""
@@ -115,8 +125,8 @@ def bench_forecast(args):
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "config 2: forecast + verify in isolation, 28 slots x 8 rows x 256 tokens x 1152 hidden, bf16, order 2",
                    "slots": slots, "rows": B, "tokens": T, "hidden": D, "order": m},
-        "roofline": {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "traffic": None,
-                     "kernel": "forecast", "launches": p["launches"], "avg_launch_us": 1e3 * p["ms"] / p["launches"],
+        "roofline": {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS,
+                     "traffic": MEASURED_TRAFFIC[("forecast", "forecast")], "kernel": "forecast", "launches": p["launches"], "avg_launch_us": 1e3 * p["ms"] / p["launches"],
                      "bytes_per_launch": p["bytes"] / p["launches"]},
         "cpu_baseline": cpu,
         "extras": {"accepted": [bool(a) for a in acc], "errors": [float(e) for e in err],
@@ -315,6 +325,7 @@ def main():
     else:
         ach = p["bytes"] / (p["ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "traffic": None}
+    roof["traffic"] = MEASURED_TRAFFIC.get(("dit_xl2", dom))
     roof.update({"kernel": dom, "launches": p["launches"], "avg_launch_us": 1e3 * p["ms"] / max(p["launches"], 1),
                  "flops_per_launch": p["flops"] / max(p["launches"], 1), "bytes_per_launch": p["bytes"] / max(p["launches"], 1)})
 
