@@ -15,6 +15,17 @@
 // regardless of M, of the tile shape and of which rows share the launch.
 // Tiles are numbered so that the 8 XCDs (round-robin block dispatch) each work on a
 // contiguous range of tiles that share activations in their own L2.
+//
+// Two main loops share the tile numbering and the epilogue:
+//   gemm_dlds_kernel  operands go global -> LDS directly (global_load_lds_dwordx4: a wave writes 64
+//                     consecutive 16-byte chunks at a wave-uniform LDS address), no register staging,
+//                     no LDS stores; unpadded 128-byte LDS rows with an XOR swizzle of the chunk
+//                     position; ring of NS stages with one raw barrier per K-step and an exact
+//                     vmcnt wait.  Needs K % 64 == 0.  Tiles 256x128 and 256x256 (half the L2 -> LDS
+//                     bytes per FLOP of 128x128).
+//   gemm_mfma_kernel  the register-staged loop described above: K tails, small problems.
+#include <cstdlib>
+
 #include "epilogue.h"
 #include "gemm.h"
 
@@ -29,6 +40,137 @@ constexpr int BK = 64;
 constexpr int LDS_STRIDE = BK + 8;   // elements; 144-byte rows
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // first-class vector: stays in registers
+
+// XCD-aware tile id: blocks b, b+8, b+16, ... run on the same XCD; give them neighbouring tiles
+// (the grid is rounded up to a multiple of 8; surplus blocks leave at once).  Inside an XCD's
+// range tiles are walked in groups of group_m M-panels, N fastest across the group's panels,
+// so that the tiles in flight at one time form a compact rectangle and share operand panels
+// in that XCD's L2.
+__device__ __forceinline__ bool tile_coords(int tiles_m, int tiles_n, int group_m, int* tm, int* tn) {
+  const int bid = blockIdx.x;
+  const int per_xcd = gridDim.x / 8;
+  const int tile = (bid % 8) * per_xcd + bid / 8;
+  if (tile >= tiles_m * tiles_n) return false;
+  const int per_group = group_m * tiles_n;
+  const int g = tile / per_group;
+  const int first = g * group_m;
+  const int h = tiles_m - first < group_m ? tiles_m - first : group_m;
+  const int r = tile - g * per_group;
+  *tm = first + r % h;
+  *tn = r / h;
+  return true;
+}
+
+// Epilogue of one block tile.  acc[i][j][4*jj + ii] = C[m][n] with m = wm*WM + j*32 + l32,
+// n = wn*WN + i*32 + 8*jj + 4*lhi + ii inside the tile.  The tile goes through LDS (fp32, rows padded
+// by 16 bytes: conflict-free for the 16-byte writes of 16 consecutive lanes), EH rows at a time, so
+// that every global access of the epilogue is a contiguous run along n: a half-wave covers one
+// 512-byte (fp32) / 256-byte (bf16) row segment.  Cs must hold EH x (BN + 4) floats; the operand
+// buffers it overlays must be dead (all waves past their last read, no load in flight).
+template <int BM, int BN, int WGM, int WGN, int MODE, int EH>
+__device__ __forceinline__ void tile_epilogue(floatx16 (&acc)[BN / WGN / 32][BM / WGM / 32], float* Cs, int m0, int n0, int M, int N,
+                                              const GemmEpi& epi) {
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int CST = BN + 4;                        // floats per staged row
+  constexpr int QPR = BN / 4;                        // quads per row
+  constexpr int RPP = NT / QPR;                      // rows per pass
+  constexpr int PASSES = EH / RPP;
+  static_assert(BM % EH == 0 && EH % WM == 0 && NT % QPR == 0 && EH % RPP == 0, "epilogue shape");
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int qc = (tid % QPR) * 4, qr = tid / QPR;
+  const int n = n0 + qc;
+  const bool live = n < N;
+  float bias[4] = {0.f, 0.f, 0.f, 0.f};
+  if (live && epi.bias) Store4<bf16_t>::ld(static_cast<const bf16_t*>(epi.bias) + n, bias);
+  // block-uniform row table when the whole tile lies inside one batch row: scalar loads
+  const int m_last = (m0 + BM < M ? m0 + BM : M) - 1;
+  int i_first = 0;
+  bool uniform = false;
+  BranchRow<bf16_t> br;
+  if (MODE == EPI_BRANCH) {
+    i_first = m0 / epi.tokens;
+    uniform = i_first == m_last / epi.tokens;
+    if (uniform) br = branch_row<bf16_t>(epi, i_first, m0);
+  }
+#pragma unroll 1
+  for (int h = 0; h < BM / EH; ++h) {
+    __syncthreads();                                 // operand buffers / previous part consumed
+    if (wm * WM / EH == h) {
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) {
+            const int r = wm * WM - h * EH + j * 32 + l32, c = wn * WN + i * 32 + 8 * jj + 4 * lhi;
+            *reinterpret_cast<float4*>(Cs + r * CST + c) =
+                make_float4(acc[i][j][4 * jj], acc[i][j][4 * jj + 1], acc[i][j][4 * jj + 2], acc[i][j][4 * jj + 3]);
+          }
+    }
+    __syncthreads();
+    if (!live) continue;
+    const int mh = m0 + h * EH;                      // first global row of this part
+    if (MODE == EPI_BRANCH) {
+      // batches of EB rows: all loads of the batch are issued before its first store
+      // (fewer when the accumulators of a later part are still live: 128 registers for a 64x128 wave tile)
+      constexpr int EBMAX = (BM / EH > 1) ? 1 : 4;
+      constexpr int EB = PASSES % EBMAX == 0 ? EBMAX : (PASSES % 2 == 0 ? 2 : 1);
+      if (uniform) {
+        for (int p0 = 0; p0 < PASSES; p0 += EB) {
+          BranchRegs<bf16_t> regs[EB];
+#pragma unroll
+          for (int u = 0; u < EB; ++u) {
+            const int r = qr + (p0 + u) * RPP;
+            if (mh + r < M) branch_load_u<bf16_t>(epi, br, h * EH + r, mh + r, n, regs[u]);
+          }
+#pragma unroll
+          for (int u = 0; u < EB; ++u) {
+            const int r = qr + (p0 + u) * RPP;
+            if (mh + r < M) {
+              const float4 t = *reinterpret_cast<const float4*>(Cs + r * CST + qc);
+              const float v[4] = {t.x + bias[0], t.y + bias[1], t.z + bias[2], t.w + bias[3]};
+              branch_finish_u<bf16_t>(epi, br, h * EH + r, mh + r, n, v, regs[u]);
+            }
+          }
+        }
+      } else {
+        for (int p0 = 0; p0 < PASSES; p0 += EB) {
+          BranchRegs<bf16_t> regs[EB];
+#pragma unroll
+          for (int u = 0; u < EB; ++u) {
+            const int m = mh + qr + (p0 + u) * RPP;
+            if (m < M) branch_load<bf16_t>(epi, m, n, regs[u]);
+          }
+#pragma unroll
+          for (int u = 0; u < EB; ++u) {
+            const int r = qr + (p0 + u) * RPP;
+            const int m = mh + r;
+            if (m < M) {
+              const float4 t = *reinterpret_cast<const float4*>(Cs + r * CST + qc);
+              const float v[4] = {t.x + bias[0], t.y + bias[1], t.z + bias[2], t.w + bias[3]};
+              branch_finish<bf16_t>(epi, m, n, v, regs[u]);
+            }
+          }
+        }
+      }
+    } else {
+#pragma unroll 4
+      for (int r = qr; r < EH; r += RPP) {
+        const int m = mh + r;
+        if (m < M) {
+          const float4 t = *reinterpret_cast<const float4*>(Cs + r * CST + qc);
+          float v[4] = {t.x + bias[0], t.y + bias[1], t.z + bias[2], t.w + bias[3]};
+          epilogue_apply<bf16_t, MODE>(epi, m, n, v);
+        }
+      }
+    }
+  }
+}
 
 // KTAIL: K is not a multiple of BK; the last operand tile is zero-filled by predicated loads.
 // SF ("store first"): the LDS stores of the next tile are issued ahead of the MFMAs of the current
@@ -48,25 +190,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const uint16_t
   uint16_t* As = smem;                              // [2][BM][LDS_STRIDE]
   uint16_t* Ws = smem + 2 * BM * LDS_STRIDE;        // [2][BN][LDS_STRIDE]
 
-  // XCD-aware tile id: blocks b, b+8, b+16, ... run on the same XCD; give them neighbouring tiles
-  // (the grid is rounded up to a multiple of 8; surplus blocks leave at once).  Inside an XCD's
-  // range tiles are walked in groups of group_m M-panels, N fastest across the group's panels,
-  // so that the tiles in flight at one time form a compact rectangle and share operand panels
-  // in that XCD's L2.
-  const int bid = blockIdx.x;
-  const int per_xcd = gridDim.x / 8;
-  const int tile = (bid % 8) * per_xcd + bid / 8;
-  if (tile >= tiles_m * tiles_n) return;
   int tm, tn;
-  {
-    const int per_group = group_m * tiles_n;
-    const int g = tile / per_group;
-    const int first = g * group_m;
-    const int h = tiles_m - first < group_m ? tiles_m - first : group_m;
-    const int r = tile - g * per_group;
-    tm = first + r % h;
-    tn = r / h;
-  }
+  if (!tile_coords(tiles_m, tiles_n, group_m, &tm, &tn)) return;
   const int m0 = tm * BM, n0 = tn * BN;
 
   const int tid = threadIdx.x;
@@ -177,87 +302,195 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const uint16_t
 #undef SPECA_STOREL
 #undef SPECA_COMPUTE
 
-  // epilogue.  acc[i][j][4*jj + ii] = C[m][n] with m = wm*WM + j*32 + l32, n = wn*WN + i*32 + 8*jj + 4*lhi + ii
-  // inside the tile.  The tile goes through LDS once (fp32, rows padded by 16 bytes: conflict-free for
-  // the 16-byte writes of 16 consecutive lanes) so that every global access of the epilogue is a
-  // contiguous run along n: a half-wave covers one 512-byte (fp32) / 256-byte (bf16) row segment.
-  constexpr int CST = BN + 4;                        // floats per staged row
-  float* Cs = reinterpret_cast<float*>(smem);        // [BM][CST]; the operand buffers are dead by now
+  tile_epilogue<BM, BN, WGM, WGN, MODE, BM>(acc, reinterpret_cast<float*>(smem), m0, n0, M, N, epi);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Direct-to-LDS main loop.
+//
+// LDS stage = [BM + BN rows][64 bf16], rows unpadded (128 bytes = 8 chunks of 16 bytes).  Chunk c of
+// row r sits at chunk position c ^ swz(r), swz(r) = (r & 7) ^ ((r >> 3) & 1): the 16 lanes that read
+// the same chunk index of 16 consecutive rows then touch all 64 banks exactly once.
+// Loader: one load instruction fills 8 rows (64 chunks, 1 KiB, contiguous in LDS); lane l supplies
+// the chunk stored at position l % 8 of row l / 8, i.e. source chunk (l % 8) ^ swz(row), and the
+// hardware places lane l's 16 bytes at the wave-uniform LDS address + 16 l.  Wave w owns the row
+// groups w, w + NW, ...; NW is even, so swz depends only on the lane and the wave's parity.
+// Rows beyond M / N are clamped to the last row (never stored), K-steps beyond the last re-read
+// the last one into a stage nobody reads again, so every wave issues the same number of loads per
+// step and "all but the newest (NS-2) steps have landed" is one immediate vmcnt value.
+// Ring discipline per K-step: wait own loads of this step; barrier (everyone's loads of this step
+// are in LDS and everyone is done reading the previous step's stage); issue the loads of step
+// kt + NS - 1 into the stage just freed; compute.
+#define SPECA_GLL(src, dst)                                                                                       \
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),                         \
+                                   (__attribute__((address_space(3))) void*)(dst), 16, 0, 0)
+
+// Rows of the tile staged through LDS per epilogue part: the whole tile when it fits into the ring's
+// LDS, else half of it (no LDS beyond the ring: 128x128 stays at 64 KiB, two blocks per CU with room).
+constexpr int dlds_epilogue_rows(int BM, int BN, int NS) {
+  return BM * (BN + 4) * 4 <= NS * (BM + BN) * BK * 2 ? BM : BM / 2;
+}
+
+template <int BM, int BN, int WGM, int WGN, int NS, int MODE>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t* __restrict__ A, int64_t lda,
+                                                                   const uint16_t* __restrict__ W, int64_t ldw, int M, int N, int K,
+                                                                   int tiles_m, int tiles_n, int group_m, GemmEpi epi) {
+  constexpr int NW = WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int AG = BM / 8 / NW, WG = BN / 8 / NW;         // 8-row groups (one load instruction each) per wave
+  static_assert(BM / 8 % NW == 0 && BN / 8 % NW == 0 && NW % 2 == 0, "row groups must divide among an even number of waves");
+  static_assert(NS == 2 || NS == 3, "ring depth");
+  constexpr int STAGE = (BM + BN) * BK;                      // elements per stage
+  constexpr int EH = dlds_epilogue_rows(BM, BN, NS);
+  extern __shared__ __align__(16) uint16_t smem[];
+
+  int tm, tn;
+  if (!tile_coords(tiles_m, tiles_n, group_m, &tm, &tn)) return;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int l32 = lane & 31, lhi = lane >> 5;
+
+  floatx16 acc[TN][TM];
 #pragma unroll
-  for (int j = 0; j < TM; ++j)
+  for (int i = 0; i < TN; ++i)
 #pragma unroll
-    for (int i = 0; i < TN; ++i)
+    for (int j = 0; j < TM; ++j)
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int r = wm * WM + j * 32 + l32, c = wn * WN + i * 32 + 8 * jj + 4 * lhi;
-        *reinterpret_cast<float4*>(Cs + r * CST + c) =
-            make_float4(acc[i][j][4 * jj], acc[i][j][4 * jj + 1], acc[i][j][4 * jj + 2], acc[i][j][4 * jj + 3]);
-      }
-  __syncthreads();
-  constexpr int QPR = BN / 4;                        // quads per row
-  constexpr int RPP = NT / QPR;                      // rows per pass
-  constexpr int PASSES = BM / RPP;
-  const int qc = (tid % QPR) * 4, qr = tid / QPR;
-  const int n = n0 + qc;
-  if (n >= N) return;
-  float bias[4] = {0.f, 0.f, 0.f, 0.f};
-  if (epi.bias) Store4<bf16_t>::ld(static_cast<const bf16_t*>(epi.bias) + n, bias);
-  if (MODE == EPI_BRANCH) {
-    // batches of EB rows: all loads of the batch are issued before its first store
-    constexpr int EB = PASSES % 4 == 0 ? 4 : (PASSES % 2 == 0 ? 2 : 1);
-    const int m_last = (m0 + BM < M ? m0 + BM : M) - 1;
-    const int i_first = m0 / epi.tokens;
-    if (i_first == m_last / epi.tokens) {
-      // the whole tile lies inside one batch row: block-uniform row table, scalar loads
-      const BranchRow<bf16_t> br = branch_row<bf16_t>(epi, i_first, m0);
-      for (int p0 = 0; p0 < PASSES; p0 += EB) {
-        BranchRegs<bf16_t> regs[EB];
+      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;
+
+  const int nk = K / BK;
+  const int lrow = lane >> 3;
+  const int lchunk = (lane & 7) ^ lrow ^ (wave & 1);
+  const uint16_t* pa[AG];
+  const uint16_t* pw[WG];
 #pragma unroll
-        for (int u = 0; u < EB; ++u) {
-          const int r = qr + (p0 + u) * RPP;
-          if (m0 + r < M) branch_load_u<bf16_t>(epi, br, r, m0 + r, n, regs[u]);
-        }
+  for (int g = 0; g < AG; ++g) {
+    const int row = (wave + g * NW) * 8 + lrow;
+    const int m = m0 + row < M ? m0 + row : M - 1;
+    pa[g] = A + static_cast<int64_t>(m) * lda + lchunk * 8;
+  }
 #pragma unroll
-        for (int u = 0; u < EB; ++u) {
-          const int r = qr + (p0 + u) * RPP;
-          if (m0 + r < M) {
-            const float4 t = *reinterpret_cast<const float4*>(Cs + r * CST + qc);
-            const float v[4] = {t.x + bias[0], t.y + bias[1], t.z + bias[2], t.w + bias[3]};
-            branch_finish_u<bf16_t>(epi, br, r, m0 + r, n, v, regs[u]);
-          }
-        }
-      }
-    } else {
-      for (int p0 = 0; p0 < PASSES; p0 += EB) {
-        BranchRegs<bf16_t> regs[EB];
+  for (int g = 0; g < WG; ++g) {
+    const int row = (wave + g * NW) * 8 + lrow;
+    const int n = n0 + row < N ? n0 + row : N - 1;
+    pw[g] = W + static_cast<int64_t>(n) * ldw + lchunk * 8;
+  }
+  // reader: row = base + l32 (bases are multiples of 32), chunk 2 ks + lhi
+  const int sw = (l32 & 7) ^ ((l32 >> 3) & 1);
+  int coff[BK / 16];
 #pragma unroll
-        for (int u = 0; u < EB; ++u) {
-          const int m = m0 + qr + (p0 + u) * RPP;
-          if (m < M) branch_load<bf16_t>(epi, m, n, regs[u]);
-        }
+  for (int ks = 0; ks < BK / 16; ++ks) coff[ks] = ((2 * ks + lhi) ^ sw) * 8;
+
+#define SPECA_LOADS(st, kt_)                                                                                      \
+  {                                                                                                               \
+    const int k0_ = ((kt_) < nk ? (kt_) : nk - 1) * BK;                                                           \
+    _Pragma("unroll") for (int g = 0; g < AG; ++g) SPECA_GLL(pa[g] + k0_, smem + (st) * STAGE + (wave + g * NW) * 512);           \
+    _Pragma("unroll") for (int g = 0; g < WG; ++g) SPECA_GLL(pw[g] + k0_, smem + (st) * STAGE + BM * BK + (wave + g * NW) * 512); \
+  }
+#define SPECA_LDFRAG(fa_, fw_, ks_)                                                                               \
+  {                                                                                                               \
+    _Pragma("unroll") for (int j = 0; j < TM; ++j) fa_[j] = *reinterpret_cast<const bf16x8*>(as + j * 32 * BK + coff[ks_]); \
+    _Pragma("unroll") for (int i = 0; i < TN; ++i) fw_[i] = *reinterpret_cast<const bf16x8*>(ws + i * 32 * BK + coff[ks_]); \
+  }
+#define SPECA_MFMAS(fa_, fw_)                                                                                     \
+  {                                                                                                               \
+    _Pragma("unroll") for (int i = 0; i < TN; ++i) _Pragma("unroll") for (int j = 0; j < TM; ++j)                 \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw_[i], fa_[j], acc[i][j], 0, 0, 0);                    \
+  }
+  // fragments of the next 16-wide K slice are requested before the MFMAs of the current one
+#define SPECA_COMPUTE(st)                                                                                         \
+  {                                                                                                               \
+    const uint16_t* as = smem + (st) * STAGE + (wm * WM + l32) * BK;                                              \
+    const uint16_t* ws = smem + (st) * STAGE + BM * BK + (wn * WN + l32) * BK;                                    \
+    bf16x8 fa0[TM], fw0[TN], fa1[TM], fw1[TN];                                                                    \
+    SPECA_LDFRAG(fa0, fw0, 0);                                                                                    \
+    SPECA_LDFRAG(fa1, fw1, 1);                                                                                    \
+    SPECA_MFMAS(fa0, fw0);                                                                                        \
+    SPECA_LDFRAG(fa0, fw0, 2);                                                                                    \
+    SPECA_MFMAS(fa1, fw1);                                                                                        \
+    SPECA_LDFRAG(fa1, fw1, 3);                                                                                    \
+    SPECA_MFMAS(fa0, fw0);                                                                                        \
+    SPECA_MFMAS(fa1, fw1);                                                                                        \
+  }
+  constexpr int LPW = AG + WG;                               // load instructions per wave per step
+  constexpr int VM = (NS - 2) * LPW;                         // loads that may still be in flight at the wait
+  static_assert(VM < 64, "vmcnt range");
+  constexpr int WAIT_VM = (VM & 0xF) | ((VM >> 4) << 14) | 0x0F70;   // s_waitcnt vmcnt(VM), other counters untouched
+  constexpr int WAIT_VM0 = 0x0F70;
+#define SPECA_STEP(st_cur, st_new, kt_)                                                                           \
+  {                                                                                                               \
+    __builtin_amdgcn_s_waitcnt(WAIT_VM);                                                                          \
+    __builtin_amdgcn_s_barrier();                                                                                 \
+    SPECA_LOADS(st_new, (kt_) + NS - 1);                                                                          \
+    SPECA_COMPUTE(st_cur);                                                                                        \
+  }
 #pragma unroll
-        for (int u = 0; u < EB; ++u) {
-          const int r = qr + (p0 + u) * RPP;
-          const int m = m0 + r;
-          if (m < M) {
-            const float4 t = *reinterpret_cast<const float4*>(Cs + r * CST + qc);
-            const float v[4] = {t.x + bias[0], t.y + bias[1], t.z + bias[2], t.w + bias[3]};
-            branch_finish<bf16_t>(epi, m, n, v, regs[u]);
-          }
-        }
-      }
+  for (int s = 0; s < NS - 1; ++s) SPECA_LOADS(s, s);
+  if (NS == 3) {
+    int kt = 0;
+    for (; kt + 3 <= nk; kt += 3) {
+      SPECA_STEP(0, 2, kt);
+      SPECA_STEP(1, 0, kt + 1);
+      SPECA_STEP(2, 1, kt + 2);
+    }
+    if (kt < nk) {
+      SPECA_STEP(0, 2, kt);
+      if (kt + 1 < nk) SPECA_STEP(1, 0, kt + 1);
     }
   } else {
-#pragma unroll 4
-    for (int r = qr; r < BM; r += RPP) {
-      const int m = m0 + r;
-      if (m < M) {
-        const float4 t = *reinterpret_cast<const float4*>(Cs + r * CST + qc);
-        float v[4] = {t.x + bias[0], t.y + bias[1], t.z + bias[2], t.w + bias[3]};
-        epilogue_apply<bf16_t, MODE>(epi, m, n, v);
-      }
+    for (int kt = 0; kt < nk; kt += 2) {
+      SPECA_STEP(0, 1, kt);
+      if (kt + 1 < nk) SPECA_STEP(1, 0, kt + 1);
     }
   }
+  __builtin_amdgcn_s_waitcnt(WAIT_VM0);                      // the clamped extra loads must have landed before LDS is reused
+#undef SPECA_STEP
+#undef SPECA_COMPUTE
+#undef SPECA_MFMAS
+#undef SPECA_LDFRAG
+#undef SPECA_LOADS
+
+  tile_epilogue<BM, BN, WGM, WGN, MODE, EH>(acc, reinterpret_cast<float*>(smem), m0, n0, M, N, epi);
+}
+
+template <int BM, int BN, int WGM, int WGN, int NS>
+Error launch_dlds(const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi, hipStream_t st) {
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  const int64_t nblk = static_cast<int64_t>(tiles_m) * tiles_n;
+  if (nblk > 0x7FFFFFF0) SPECA_FAIL(SPECA_EINVAL, "gemm: too many tiles");
+  if (K % BK != 0 || K < BK) SPECA_FAIL(SPECA_EINVAL, "gemm: direct-to-LDS loop needs K %% 64 == 0");
+  constexpr int EH = dlds_epilogue_rows(BM, BN, NS);
+  const size_t smem_ops = static_cast<size_t>(NS) * (BM + BN) * BK * sizeof(uint16_t);
+  const size_t smem_epi = static_cast<size_t>(EH) * (BN + 4) * sizeof(float);
+  const size_t smem = smem_ops > smem_epi ? smem_ops : smem_epi;
+  const uint16_t* a = static_cast<const uint16_t*>(A);
+  const uint16_t* w = static_cast<const uint16_t*>(W);
+  dim3 grid(static_cast<unsigned>((nblk + 7) / 8 * 8));
+  const int group_m = tiles_m < 4 ? tiles_m : 4;
+#define SPECA_LAUNCH(MODE_)                                                                                       \
+  {                                                                                                               \
+    auto kern = gemm_dlds_kernel<BM, BN, WGM, WGN, NS, MODE_>;                                                    \
+    static bool attr_set = false;   /* more than 64 KB of dynamic LDS must be requested once per kernel */          \
+    if (smem > 64 * 1024 && !attr_set) {                                                                          \
+      SPECA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem))); \
+      attr_set = true;                                                                                            \
+    }                                                                                                             \
+    kern<<<grid, WGM * WGN * 64, smem, st>>>(a, lda, w, ldw, M, N, K, tiles_m, tiles_n, group_m, epi);             \
+  }
+  switch (epi.mode) {
+    case EPI_STORE: SPECA_LAUNCH(EPI_STORE) break;
+    case EPI_GELU: SPECA_LAUNCH(EPI_GELU) break;
+    case EPI_SILU: SPECA_LAUNCH(EPI_SILU) break;
+    case EPI_F32: SPECA_LAUNCH(EPI_F32) break;
+    case EPI_BRANCH: SPECA_LAUNCH(EPI_BRANCH) break;
+    default: SPECA_FAIL(SPECA_EINVAL, "gemm: epilogue mode %d", epi.mode);
+  }
+#undef SPECA_LAUNCH
+  SPECA_HIP(hipGetLastError());
+  return ok();
 }
 
 template <int BM, int BN, int WGM, int WGN>
@@ -312,15 +545,25 @@ bool gemm_mfma_supported(const void* A, int64_t lda, const void* W, int64_t ldw,
 }
 
 Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi, hipStream_t st) {
-  // Tile shapes, from measurements on the reference-step shapes (M = 4096, N 1152..4608):
-  //   256x128 with 8 waves (4x2, wave tile 64x64): three quarters of the operand traffic per FLOP of
-  //     a 128x128 tile at the same per-wave register cost; best when it still leaves >= 1 tile per
-  //     CU-half and, for short K loops, N is not so wide that 128x128 already fills the chip several
-  //     times over;
-  //   128x128 with 4 waves: the default for everything else that is big enough;
-  //   128x64: problems too small to give each CU a tile otherwise.
+  // Tile shapes, from measurements on the reference-step shapes (M = 4096, N 1152..4608, K 1152 / 4608)
+  // and on FLUX-sized ones (M 4608, N 3072..12288, K 3072..12288):
+  //   256x256, 8 waves (wave tile 64x128): fewest L2 -> LDS bytes per FLOP; wins once K is long and the
+  //     problem still gives most CUs a tile (one block per CU);
+  //   256x128, 8 waves, 3-stage ring: medium problems;
+  //   128x128, 4 waves, register-staged loop, two blocks per CU: wide N with short K (inside a step the
+  //     direct-to-LDS 128x128 tile measured 75 us against 65 us on the 4096 x 4608 x 1152 MLP GEMM,
+  //     although it wins in isolation: with one K-step of prefetch it is more exposed to HBM latency
+  //     while the previous kernel's cache writes drain);
+  //   128x64 (register-staged loop): problems too small to give each CU a tile otherwise, and K tails.
   const int64_t t128 = static_cast<int64_t>((M + 127) / 128) * ((N + 127) / 128);
   const int64_t t256 = static_cast<int64_t>((M + 255) / 256) * ((N + 127) / 128);
+  const int64_t t256s = static_cast<int64_t>((M + 255) / 256) * ((N + 255) / 256);
+  // SPECA_GEMM_LOOP=staged keeps every shape on the register-staged loop (A/B timing of the two loops)
+  static const bool staged_only = [] { const char* e = getenv("SPECA_GEMM_LOOP"); return e && e[0] == 's'; }();
+  if (K % BK == 0 && M >= 256 && !staged_only) {
+    if (K >= 2048 && t256s >= 200) return launch_dlds<256, 256, 4, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
+    if (t256 >= 128 && t128 <= 1024) return launch_dlds<256, 128, 4, 2, 3>(A, lda, W, ldw, M, N, K, epi, st);
+  }
   if (t256 >= 128 && (t128 <= 1024 || (K >= 2048 && t128 >= 2048)) && M >= 256) return launch_tile<256, 128, 4, 2>(A, lda, W, ldw, M, N, K, epi, st);
   if (t128 >= 200) return launch_tile<128, 128, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
   return launch_tile<128, 64, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);

@@ -40,6 +40,8 @@ def _check(got, exp, dtype, K):
 SHAPES = [  # M, N, K
     (128, 128, 64), (256, 64, 128), (200, 192, 72), (1, 64, 64), (130, 1152, 1152), (515, 256, 4608), (16, 2304, 1152),
     (300, 16, 64),
+    # the direct-to-LDS tiles, each with ragged M and N: 128x128, 256x128 (3-stage ring, K-steps 3n+1 and 3n+2), 256x256
+    (1000, 3304, 128), (4000, 1160, 256), (4000, 1160, 320), (4000, 3400, 2048),
 ]
 
 
@@ -70,6 +72,14 @@ def test_linear_row_result_independent_of_m():
     full = bd.linear(a, w)
     part = bd.linear(a[300:333].contiguous(), w)
     assert torch.equal(full[300:333], part)         # bitwise: fixed K order, no split-K
+    # the same across main loops and tile shapes: 4096 rows take the 256x128 direct-to-LDS tiles, 33 rows
+    # the register-staged 128x64 ones; K = 2048 with 4096 x 3072 outputs takes 256x256
+    a = _dev(rng.standard_normal((4096, 1152)), "bf16")
+    full = bd.linear(a, w)
+    assert torch.equal(full[1000:1033], bd.linear(a[1000:1033].contiguous(), w))
+    a = _dev(rng.standard_normal((4096, 2048)), "bf16"); w = _dev(rng.standard_normal((3072, 2048)) * 0.03, "bf16")
+    full = bd.linear(a, w)
+    assert torch.equal(full[4000:4096], bd.linear(a[4000:4096].contiguous(), w))
 
 
 @pytest.mark.parametrize("rows,T,H,hd", [(2, 16, 4, 16), (1, 100, 2, 72), (2, 256, 3, 72), (1, 77, 2, 64), (1, 300, 2, 128), (1, 64, 1, 32)])
