@@ -264,6 +264,7 @@ def main():
     ap.add_argument("--tau0", type=float, default=0.1)
     ap.add_argument("--tau-end", type=float, default=0.02)
     ap.add_argument("--interval", type=int, default=5)
+    ap.add_argument("--lanes", type=int, default=4, help="row groups of a step that run side by side (1 = serial)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -289,6 +290,7 @@ def main():
     weights = si.make_dit_weights(shape, 0)
     ctx = sp.Context(sp.dit_desc(shape), sp.to_device(weights, bd.BF16))
     ctx.init_cache(sp.make_cfg(order=order, interval=args.interval), 2 * B)
+    ctx.set_lanes(args.lanes)          # the event-profiled pass below always runs serially (clean per-kernel times)
     lat = si.make_latents(B, shape.in_channels, shape.latent_hw, 0)
     lab = si.make_labels(B, shape.num_classes, 0)
 
@@ -353,7 +355,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "config 3: DiT-XL/2-shaped bf16, batch 8 x CFG 1.5 (16 rows), 256 tokens, DDIM, Taylor order 2",
                    "global_batch": B, "rows": 2 * B, "tokens": shape.tokens, "hidden": shape.hidden, "blocks": shape.depth,
-                   "order": order, "interval": args.interval, "tau0": args.tau0, "tau_end": args.tau_end, "parallelism": "single GPU"},
+                   "order": order, "interval": args.interval, "tau0": args.tau0, "tau_end": args.tau_end, "lanes": args.lanes,
+                   "parallelism": "single GPU"},
         "roofline": roof,
         "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(shape, weights),
         "extras": extras,

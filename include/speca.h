@@ -237,6 +237,15 @@ typedef struct speca_profile {
   double  bytes[SPECA_PROF_CLASSES];   /* algorithmic: tensors the method must read + write once */
 } speca_profile;
 
+/* Lanes (an execution option, not part of the method; Sec. 3.2's steps are computed per sample, so
+ * the rows of a launch are independent).  A step runs its rows in up to `lanes` groups side by side
+ * on library-owned streams forked from and joined to the context's stream with events, so callers
+ * see the usual stream order and bit-identical results.  Default 2 (SPECA_LANES in the environment
+ * at create overrides), 1 = strictly serial, at most 4.  While a profile is open steps run serially
+ * (per-kernel event times are only meaningful without overlap) unless profile_keeps_lanes != 0.
+ * Returns SPECA_EINVAL for a value outside 1..4. */
+int speca_set_lanes(speca_ctx* ctx, int lanes, int profile_keeps_lanes);
+
 /* While a profile is open every kernel launch of the context is bracketed by a HIP event pair
  * on its stream (this serialises launches and costs a few microseconds each: time a workload
  * for throughput with the profile closed).  speca_profile_end synchronises and sums. */

@@ -97,6 +97,7 @@ def load_library() -> C.CDLL:
         "speca_sample": [vp, vp, C.c_int, C.POINTER(Cond), C.POINTER(Solver), f32p, C.POINTER(Trace)],
         "speca_linear": [vp, C.c_int, vp, C.c_int, C.c_int, vp, C.c_int, vp, C.c_int, vp],
         "speca_attention": [vp, C.c_int, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int],
+        "speca_set_lanes": [vp, C.c_int, C.c_int],
         "speca_profile_begin": [vp],
         "speca_profile_end": [vp, C.POINTER(Profile)],
         "speca_tau_geometric": [C.c_float, C.c_float, C.c_int, f32p],
@@ -121,7 +122,7 @@ def load_library() -> C.CDLL:
 
 EXPORTED = ["speca_create", "speca_destroy", "speca_last_error", "speca_init_cache", "speca_refresh",
             "speca_full_step", "speca_forecast", "speca_verify", "speca_spec_step", "speca_sample",
-            "speca_linear", "speca_attention", "speca_profile_begin", "speca_profile_end",
+            "speca_linear", "speca_attention", "speca_set_lanes", "speca_profile_begin", "speca_profile_end",
             "speca_tau_geometric", "speca_tau_linear", "speca_coefficients", "speca_divisors",
             "speca_sched_create", "speca_sched_destroy", "speca_sched_plan", "speca_sched_commit",
             "speca_sched_refs"]
@@ -324,6 +325,10 @@ class Context:
         self._ck(self.lib.speca_verify(self.h, C.c_void_p(pred.data_ptr()), C.c_void_p(truth.data_ptr()), n_rows, E, dtype,
                                        _p(t, C.c_float) if t is not None else None, eps, _p(err, C.c_float), _p(acc, C.c_uint8)))
         return err, (acc.astype(bool) if t is not None else None)
+
+    def set_lanes(self, lanes: int, profile_keeps_lanes: bool = False):
+        """Row groups of a step that run side by side on streams of the library (1 = serial)."""
+        self._ck(self.lib.speca_set_lanes(self.h, int(lanes), int(bool(profile_keeps_lanes))))
 
     def profile_begin(self):
         self._ck(self.lib.speca_profile_begin(self.h))

@@ -102,6 +102,11 @@ static bool cfg_ok(const speca_cfg* c, std::string* why) {
 static void free_ctx(speca_ctx* ctx) {
   if (!ctx) return;
   (void)hipStreamSynchronize(ctx->stream);
+  for (int k = 1; k < kMaxLanes; ++k)
+    if (ctx->lane_stream[k]) { (void)hipStreamSynchronize(ctx->lane_stream[k]); (void)hipStreamDestroy(ctx->lane_stream[k]); }
+  if (ctx->lane_fork) (void)hipEventDestroy(ctx->lane_fork);
+  for (int k = 0; k < kMaxLanes; ++k)
+    if (ctx->lane_join[k]) (void)hipEventDestroy(ctx->lane_join[k]);
   ctx->model.reset();
   if (ctx->geom.base) (void)hipFree(ctx->geom.base);
   VerifyScratch& v = ctx->vs;
@@ -137,6 +142,15 @@ static Error create_impl(speca_ctx** out, const speca_model_desc* desc, const sp
       SPECA_FAIL(SPECA_EINVAL, "model kind = %d", desc->kind);
   }
   SPECA_HIP(hipGetDevice(&ctx->device));
+  // lane streams: default priority, not synchronising with the NULL stream; ordering is by events only
+  ctx->lane_stream[0] = ctx->stream;
+  for (int k = 1; k < kMaxLanes; ++k) SPECA_HIP(hipStreamCreateWithFlags(&ctx->lane_stream[k], hipStreamNonBlocking));
+  SPECA_HIP(hipEventCreateWithFlags(&ctx->lane_fork, hipEventDisableTiming));
+  for (int k = 0; k < kMaxLanes; ++k) SPECA_HIP(hipEventCreateWithFlags(&ctx->lane_join[k], hipEventDisableTiming));
+  if (const char* e = getenv("SPECA_LANES")) {
+    const int v = atoi(e);
+    if (v >= 1 && v <= kMaxLanes) ctx->lanes = v;
+  }
   VerifyScratch& v = ctx->vs;
   SPECA_HIP(hipMalloc(&v.tau_dev, kMaxRows * sizeof(float)));
   SPECA_HIP(hipMalloc(&v.err_dev, kMaxRows * sizeof(float)));
@@ -147,6 +161,42 @@ static Error create_impl(speca_ctx** out, const speca_model_desc* desc, const sp
   *out = ctx.release();
   return ok();
 }
+
+namespace speca {
+LaneSplit split_lanes(const speca_ctx* ctx, int n, int min_rows) {
+  LaneSplit ls;
+  int k = ctx->lanes;
+  if (ctx->prof.on && !ctx->prof.keep_lanes) k = 1;
+  if (min_rows < 1) min_rows = 1;
+  while (k > 1 && n / k < min_rows) --k;
+  ls.n_lanes = k;
+  for (int i = 0; i <= k; ++i) ls.first[i] = static_cast<int>(static_cast<int64_t>(n) * i / k);
+  return ls;
+}
+Error lanes_fork(speca_ctx* ctx, const LaneSplit& ls) {
+  if (ls.n_lanes <= 1) return ok();
+  SPECA_HIP(hipEventRecord(ctx->lane_fork, ctx->stream));
+  for (int k = 1; k < ls.n_lanes; ++k) SPECA_HIP(hipStreamWaitEvent(ctx->lane_stream[k], ctx->lane_fork, 0));
+  return ok();
+}
+Error lanes_join(speca_ctx* ctx, const LaneSplit& ls) {
+  for (int k = 1; k < ls.n_lanes; ++k) {
+    SPECA_HIP(hipEventRecord(ctx->lane_join[k], ctx->lane_stream[k]));
+    SPECA_HIP(hipStreamWaitEvent(ctx->stream, ctx->lane_join[k], 0));
+  }
+  return ok();
+}
+RowTable slice_table(const RowTable& rt, int first, int n) {
+  RowTable o{};
+  o.n = n;
+  for (int i = 0; i < n; ++i) {
+    o.row[i] = rt.row[first + i];
+    o.order[i] = rt.order[first + i];
+    for (int q = 0; q < kMaxTensors; ++q) o.w[i][q] = rt.w[first + i][q];
+  }
+  return o;
+}
+}  // namespace speca
 
 static Error init_cache_impl(speca_ctx* ctx, const speca_cfg* cfg, int batch_rows) {
   std::string why;
@@ -324,6 +374,14 @@ int speca_destroy(speca_ctx* ctx) {
 }
 
 const char* speca_last_error(const speca_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+int speca_set_lanes(speca_ctx* ctx, int lanes, int profile_keeps_lanes) {
+  if (!ctx) return SPECA_EINVAL;
+  if (lanes < 1 || lanes > kMaxLanes) return finish(ctx, [&]() -> Error { SPECA_FAIL(SPECA_EINVAL, "lanes = %d (1..%d)", lanes, kMaxLanes); }());
+  ctx->lanes = lanes;
+  ctx->prof.keep_lanes = profile_keeps_lanes != 0;
+  return SPECA_OK;
+}
 
 int speca_init_cache(speca_ctx* ctx, const speca_cfg* cfg, int batch_rows) {
   if (!ctx) return SPECA_EINVAL;

@@ -16,6 +16,7 @@ namespace speca {
 
 constexpr int kMaxTensors = SPECA_MAX_ORDER + 1;   // D^0 .. D^m
 constexpr int kMaxRows = SPECA_MAX_LAUNCH_ROWS;
+constexpr int kMaxLanes = 4;   // concurrent row groups of one step
 
 // ---- storage types -----------------------------------------------------------------
 // bf16 values travel as raw 16-bit patterns; arithmetic is always fp32.

@@ -42,6 +42,15 @@ struct speca_ctx {
   size_t cache_cap = 0;                       // bytes allocated at geom.base
   std::vector<speca::RefHistory> row_refs;    // per cache row
 
+  // Lanes: the rows of one launch are independent, so a step can run its row groups side by side
+  // on streams of its own (lane 0 is `stream`).  While one group sits in an HBM-bound epilogue or
+  // LayerNorm the other keeps the matrix cores busy, and two half-size GEMMs together fill the CUs
+  // that one tile-quantised launch leaves idle.  Fork / join with events; results do not change.
+  int lanes = 2;
+  hipStream_t lane_stream[speca::kMaxLanes] = {};   // [0] = stream; others library-owned
+  hipEvent_t lane_fork = nullptr;
+  hipEvent_t lane_join[speca::kMaxLanes] = {};
+
   speca::VerifyScratch vs;
   std::unique_ptr<speca::Model> model;
   speca::Profiler prof;
@@ -54,9 +63,26 @@ namespace speca {
 // Brackets the launches made in its scope with an event pair when a profile is open.
 struct ProfScope {
   speca_ctx* c;
-  ProfScope(speca_ctx* ctx, int cls, double flops, double bytes) : c(ctx) { c->prof.begin(cls, flops, bytes, c->stream); }
-  ~ProfScope() { c->prof.end(c->stream); }
+  hipStream_t st;
+  ProfScope(speca_ctx* ctx, int cls, double flops, double bytes) : c(ctx), st(ctx->stream) { c->prof.begin(cls, flops, bytes, st); }
+  ProfScope(speca_ctx* ctx, hipStream_t stream, int cls, double flops, double bytes) : c(ctx), st(stream) { c->prof.begin(cls, flops, bytes, st); }
+  ~ProfScope() { c->prof.end(st); }
 };
+
+// Row groups of one launch: lane k takes compact rows [first[k], first[k+1]).
+struct LaneSplit {
+  int n_lanes = 1;
+  int first[kMaxLanes + 1] = {};
+};
+// Split n rows over the context's lanes (at least min_rows per lane; one lane while a profile is open
+// unless the caller asked for lanes explicitly: per-kernel event times are only clean when serial).
+LaneSplit split_lanes(const speca_ctx* ctx, int n, int min_rows);
+// main stream -> all lanes of the split (they wait for everything enqueued on the main stream so far)
+Error lanes_fork(speca_ctx* ctx, const LaneSplit& ls);
+// all lanes -> main stream
+Error lanes_join(speca_ctx* ctx, const LaneSplit& ls);
+// Rows [first, first + n) of a table, as a table of its own.
+RowTable slice_table(const RowTable& rt, int first, int n);
 inline double table_tensors(const RowTable& rt) {   // sum over rows of (order + 1)
   double t = 0;
   for (int i = 0; i < rt.n; ++i) t += rt.order[i] + 1;

@@ -168,61 +168,108 @@ struct DiT final : Model {
     return launch_patch_embed(d.dtype, x, xr, patch_w, patch_b, pos, h, n, d.in_channels, d.latent_h, d.latent_w, d.patch, D, st);
   }
 
-  const float* mod_at(int l, int which) const { return mod + static_cast<int64_t>(l) * 6 * D + static_cast<int64_t>(which) * D; }
+  // A lane works on compact rows [o, o + n) of every workspace buffer, on its own stream.
+  struct Lane {
+    hipStream_t st;
+    int o;
+  };
+  const float* mod_at(int l, int which, int o = 0) const {
+    return mod + static_cast<int64_t>(o) * mod_n + static_cast<int64_t>(l) * 6 * D + static_cast<int64_t>(which) * D;
+  }
+  template <typename P> P* at(P* base, const Lane& ln, int64_t per_row_bytes) const {
+    return reinterpret_cast<P*>(reinterpret_cast<char*>(base) + static_cast<int64_t>(ln.o) * per_row_bytes);
+  }
 
-  // attention branch of block l on hidden state hs: hs += gate_a * proj(MHA(LNmod(hs)))
-  Error attn_branch(speca_ctx* ctx, int l, float* hs, int n, const RowTable* refresh_rt) {
-    hipStream_t st = ctx->stream;
+  // attention branch of block l on the lane's rows of hidden state hs (hs = row 0 of the buffer):
+  // hs += gate_a * proj(MHA(LNmod(hs)))
+  Error attn_branch(speca_ctx* ctx, const Lane& ln, int l, float* hs, int n, const RowTable* refresh_rt) {
+    hipStream_t st = ln.st;
     const int64_t M = static_cast<int64_t>(n) * T;
     const double Md = static_cast<double>(M);
+    const int64_t TD = static_cast<int64_t>(T) * D;
+    float* hl = hs + ln.o * TD;
+    void* xn_l = at(static_cast<char*>(xn), ln, TD * esz);
+    void* qkv_l = at(static_cast<char*>(qkv), ln, 3 * TD * esz);
+    void* att_l = at(static_cast<char*>(att), ln, TD * esz);
     {
-      ProfScope ps(ctx, SPECA_PROF_OTHER, 0.0, Md * D * (4 + esz));
-      SPECA_TRY(launch_ln_modulate(d.dtype, hs, mod_at(l, 0), mod_at(l, 1), mod_n, xn, M, T, D, st));
+      ProfScope ps(ctx, st, SPECA_PROF_OTHER, 0.0, Md * D * (4 + esz));
+      SPECA_TRY(launch_ln_modulate(d.dtype, hl, mod_at(l, 0, ln.o), mod_at(l, 1, ln.o), mod_n, xn_l, M, T, D, st));
     }
     GemmEpi e;
-    e.mode = EPI_STORE; e.bias = blk[l].qkv_b; e.out = qkv; e.ldo = 3 * D;
+    e.mode = EPI_STORE; e.bias = blk[l].qkv_b; e.out = qkv_l; e.ldo = 3 * D;
     {
-      ProfScope ps(ctx, SPECA_PROF_GEMM, 2.0 * Md * 3 * D * D, (Md * 4 * D + 3.0 * D * D) * esz);
-      SPECA_TRY(launch_gemm(d.dtype, xn, D, blk[l].qkv_w, D, static_cast<int>(M), 3 * D, D, e, st));
+      ProfScope ps(ctx, st, SPECA_PROF_GEMM, 2.0 * Md * 3 * D * D, (Md * 4 * D + 3.0 * D * D) * esz);
+      SPECA_TRY(launch_gemm(d.dtype, xn_l, D, blk[l].qkv_w, D, static_cast<int>(M), 3 * D, D, e, st));
     }
     {
-      ProfScope ps(ctx, SPECA_PROF_ATTENTION, 4.0 * n * H * static_cast<double>(T) * T * hd, Md * 4 * D * esz);
-      SPECA_TRY(launch_attention(d.dtype, qkv, att, D, n, T, H, hd, st));
+      ProfScope ps(ctx, st, SPECA_PROF_ATTENTION, 4.0 * n * H * static_cast<double>(T) * T * hd, Md * 4 * D * esz);
+      SPECA_TRY(launch_attention(d.dtype, qkv_l, att_l, D, n, T, H, hd, st));
     }
     GemmEpi b;
-    b.mode = EPI_BRANCH; b.bias = blk[l].proj_b; b.h = hs; b.ldh = D; b.gate = mod_at(l, 2); b.gate_stride = mod_n; b.tokens = T;
+    b.mode = EPI_BRANCH; b.bias = blk[l].proj_b; b.h = hl; b.ldh = D; b.gate = mod_at(l, 2, ln.o); b.gate_stride = mod_n; b.tokens = T;
     if (refresh_rt) { b.refresh = 1; b.slot = 2 * l; b.g = ctx->geom; b.rt = *refresh_rt; }
-    ProfScope ps(ctx, SPECA_PROF_GEMM, 2.0 * Md * D * D, (Md * D + 1.0 * D * D) * esz + Md * D * 8);
-    SPECA_TRY(launch_gemm(d.dtype, att, D, blk[l].proj_w, D, static_cast<int>(M), D, D, b, st));
+    ProfScope ps(ctx, st, SPECA_PROF_GEMM, 2.0 * Md * D * D, (Md * D + 1.0 * D * D) * esz + Md * D * 8);
+    SPECA_TRY(launch_gemm(d.dtype, att_l, D, blk[l].proj_w, D, static_cast<int>(M), D, D, b, st));
     return ok();
   }
 
-  // MLP branch of block l.  truth_out != nullptr: only materialise F_mlp (fp32) there, no residual, no refresh.
-  Error mlp_branch(speca_ctx* ctx, int l, float* hs, int n, const RowTable* refresh_rt, float* truth_out) {
-    hipStream_t st = ctx->stream;
+  // MLP branch of block l on the lane's rows.  truth_out != nullptr (row 0 of the buffer): only materialise
+  // F_mlp (fp32) there, no residual, no refresh.
+  Error mlp_branch(speca_ctx* ctx, const Lane& ln, int l, float* hs, int n, const RowTable* refresh_rt, float* truth_out) {
+    hipStream_t st = ln.st;
     const int64_t M = static_cast<int64_t>(n) * T;
     const double Md = static_cast<double>(M);
+    const int64_t TD = static_cast<int64_t>(T) * D;
+    float* hl = hs + ln.o * TD;
+    void* xn_l = at(static_cast<char*>(xn), ln, TD * esz);
+    void* f1_l = at(static_cast<char*>(f1), ln, static_cast<int64_t>(T) * Dm * esz);
     {
-      ProfScope ps(ctx, SPECA_PROF_OTHER, 0.0, Md * D * (4 + esz));
-      SPECA_TRY(launch_ln_modulate(d.dtype, hs, mod_at(l, 3), mod_at(l, 4), mod_n, xn, M, T, D, st));
+      ProfScope ps(ctx, st, SPECA_PROF_OTHER, 0.0, Md * D * (4 + esz));
+      SPECA_TRY(launch_ln_modulate(d.dtype, hl, mod_at(l, 3, ln.o), mod_at(l, 4, ln.o), mod_n, xn_l, M, T, D, st));
     }
     GemmEpi e;
-    e.mode = EPI_GELU; e.bias = blk[l].fc1_b; e.out = f1; e.ldo = Dm;
+    e.mode = EPI_GELU; e.bias = blk[l].fc1_b; e.out = f1_l; e.ldo = Dm;
     {
-      ProfScope ps(ctx, SPECA_PROF_GEMM, 2.0 * Md * Dm * D, (Md * (D + Dm) + 1.0 * D * Dm) * esz);
-      SPECA_TRY(launch_gemm(d.dtype, xn, D, blk[l].fc1_w, D, static_cast<int>(M), Dm, D, e, st));
+      ProfScope ps(ctx, st, SPECA_PROF_GEMM, 2.0 * Md * Dm * D, (Md * (D + Dm) + 1.0 * D * Dm) * esz);
+      SPECA_TRY(launch_gemm(d.dtype, xn_l, D, blk[l].fc1_w, D, static_cast<int>(M), Dm, D, e, st));
     }
     GemmEpi b;
     b.bias = blk[l].fc2_b;
     if (truth_out) {
-      b.mode = EPI_F32; b.out = truth_out; b.ldo = D;
+      b.mode = EPI_F32; b.out = truth_out + ln.o * TD; b.ldo = D;
     } else {
-      b.mode = EPI_BRANCH; b.h = hs; b.ldh = D; b.gate = mod_at(l, 5); b.gate_stride = mod_n; b.tokens = T;
+      b.mode = EPI_BRANCH; b.h = hl; b.ldh = D; b.gate = mod_at(l, 5, ln.o); b.gate_stride = mod_n; b.tokens = T;
       if (refresh_rt) { b.refresh = 1; b.slot = 2 * l + 1; b.g = ctx->geom; b.rt = *refresh_rt; }
     }
-    ProfScope ps(ctx, SPECA_PROF_GEMM, 2.0 * Md * Dm * D, (Md * Dm + 1.0 * D * Dm) * esz + Md * D * 8);
-    SPECA_TRY(launch_gemm(d.dtype, f1, Dm, blk[l].fc2_w, Dm, static_cast<int>(M), D, Dm, b, st));
+    ProfScope ps(ctx, st, SPECA_PROF_GEMM, 2.0 * Md * Dm * D, (Md * Dm + 1.0 * D * Dm) * esz + Md * D * 8);
+    SPECA_TRY(launch_gemm(d.dtype, f1_l, Dm, blk[l].fc2_w, Dm, static_cast<int>(M), D, Dm, b, st));
     return ok();
+  }
+
+  // Blocks [l0, l1) for all n rows, the row groups of the split side by side (launches interleaved
+  // block by block so the lanes stay in step).  refresh_rt / truth as in the branch functions.
+  Error run_blocks(speca_ctx* ctx, int l0, int l1, float* hs, int n, const RowTable* refresh_rt, float* truth_last_mlp) {
+    const LaneSplit ls = split_lanes(ctx, n, 2);
+    RowTable sub[kMaxLanes];
+    if (refresh_rt)
+      for (int k = 0; k < ls.n_lanes; ++k) sub[k] = slice_table(*refresh_rt, ls.first[k], ls.first[k + 1] - ls.first[k]);
+    SPECA_TRY(lanes_fork(ctx, ls));
+    Error body = [&]() -> Error {
+      for (int l = l0; l < l1; ++l) {
+        for (int k = 0; k < ls.n_lanes; ++k) {
+          const Lane ln{ctx->lane_stream[k], ls.first[k]};
+          SPECA_TRY(attn_branch(ctx, ln, l, hs, ls.first[k + 1] - ls.first[k], refresh_rt ? &sub[k] : nullptr));
+        }
+        for (int k = 0; k < ls.n_lanes; ++k) {
+          const Lane ln{ctx->lane_stream[k], ls.first[k]};
+          SPECA_TRY(mlp_branch(ctx, ln, l, hs, ls.first[k + 1] - ls.first[k], refresh_rt ? &sub[k] : nullptr,
+                               l == l1 - 1 ? truth_last_mlp : nullptr));
+        }
+      }
+      return ok();
+    }();
+    Error joined = lanes_join(ctx, ls);        // also after a failed launch: the main stream never runs ahead of a lane
+    return body.code != SPECA_OK ? body : joined;
   }
 
   Error final_layer(speca_ctx* ctx, const float* hs, const int32_t* rows, int n, float* model_out) {
@@ -246,10 +293,7 @@ struct DiT final : Model {
     SPECA_TRY(build_refresh_table(ctx, step, rows, n, &rt));
     SPECA_TRY(conditioning(ctx, cond->timestep, labels_per_row, step, rows, n));
     SPECA_TRY(embed(ctx, x, x_mod, rows, n));
-    for (int l = 0; l < L; ++l) {
-      SPECA_TRY(attn_branch(ctx, l, h, n, &rt));
-      SPECA_TRY(mlp_branch(ctx, l, h, n, &rt, nullptr));
-    }
+    SPECA_TRY(run_blocks(ctx, 0, L, h, n, &rt, nullptr));
     SPECA_TRY(final_layer(ctx, h, rows, n, model_out));
     push_refs(ctx, step, rows, n);
     return ok();
@@ -288,8 +332,7 @@ struct DiT final : Model {
       SPECA_TRY(launch_forecast_fold(ctx->geom, rt, h, h2, mod, mod_n, gate_off_dev, 0, 2 * lv, 2 * L, D, st));
     }
     // the verify block for real, on h
-    SPECA_TRY(attn_branch(ctx, lv, h, n, nullptr));
-    SPECA_TRY(mlp_branch(ctx, lv, h, n, nullptr, feat));
+    SPECA_TRY(run_blocks(ctx, lv, lv + 1, h, n, nullptr, feat));
     // Eq. 4: forecast of slot 2lv+1 (formed on the fly from the cache) vs the recomputed feature
     VerifyScratch& v = ctx->vs;
     SPECA_TRY(ensure_partial(ctx, static_cast<size_t>(n) * verify_chunks(ctx->geom.E) * 3));

@@ -43,6 +43,30 @@ template <> struct Store4<bf16_t> {
   }
 };
 
+// Streaming forms for data that is written once and read a whole step later (the cache): no reuse to
+// keep in L2.
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ inline void st4_stream(bf16_t* p, const float* v) {
+  u32x2_t r;
+  r.x = static_cast<uint32_t>(f32_to_bf16(v[0])) | (static_cast<uint32_t>(f32_to_bf16(v[1])) << 16);
+  r.y = static_cast<uint32_t>(f32_to_bf16(v[2])) | (static_cast<uint32_t>(f32_to_bf16(v[3])) << 16);
+  __builtin_nontemporal_store(r, reinterpret_cast<u32x2_t*>(p));
+}
+__device__ inline void st4_stream(float* p, const float* v) {
+  f32x4_t r = {v[0], v[1], v[2], v[3]};
+  __builtin_nontemporal_store(r, reinterpret_cast<f32x4_t*>(p));
+}
+__device__ inline void ld4_stream(const bf16_t* p, float* v) {
+  const u32x2_t r = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
+  v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xFFFF0000u);
+  v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xFFFF0000u);
+}
+__device__ inline void ld4_stream(const float* p, float* v) {
+  const f32x4_t r = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+  v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
+}
+
 template <typename T, int MODE>
 __device__ inline void epilogue_apply(const GemmEpi& e, int m, int n, float v[4]);
 
@@ -194,29 +218,29 @@ __device__ inline void branch_load_u(const GemmEpi& e, const BranchRow<T>& b, in
   const int64_t pos = static_cast<int64_t>(b.t0 + r) * e.ldh + n;
 #pragma unroll
   for (int o = 0; o < SPECA_MAX_ORDER; ++o)
-    if (o < b.order) Store4<T>::ld(b.d[o] + pos, regs.old[o]);
-  Store4<float>::ld(b.gate + n, regs.g);
-  Store4<float>::ld(e.h + static_cast<int64_t>(m) * e.ldh + n, regs.hv);
+    if (o < b.order) ld4_stream(b.d[o] + pos, regs.old[o]);
+  Store4<float>::ld(e.h + static_cast<int64_t>(m) * e.ldh + n, regs.hv);    // the gate is per (batch row, n): the caller holds it
 }
 
 template <typename T>
-__device__ inline void branch_finish_u(const GemmEpi& e, const BranchRow<T>& b, int r, int m, int n, const float v[4], BranchRegs<T>& regs) {
+__device__ inline void branch_finish_u(const GemmEpi& e, const BranchRow<T>& b, int r, int m, int n, const float v[4], const float g[4],
+                                       BranchRegs<T>& regs) {
   if (b.refresh) {
     const int64_t pos = static_cast<int64_t>(b.t0 + r) * e.ldh + n;
     float cur[4] = {v[0], v[1], v[2], v[3]};
-    Store4<T>::st(b.d[0] + pos, cur);
+    st4_stream(b.d[0] + pos, cur);
 #pragma unroll
     for (int o = 1; o <= SPECA_MAX_ORDER; ++o)
       if (o <= b.order) {
         const float inv = b.inv[o - 1];
 #pragma unroll
         for (int q = 0; q < 4; ++q) cur[q] = (cur[q] - regs.old[o - 1][q]) * inv;
-        Store4<T>::st(b.d[o] + pos, cur);
+        st4_stream(b.d[o] + pos, cur);
       }
   }
   float hv[4];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) hv[q] = fmaf(regs.g[q], v[q], regs.hv[q]);
+  for (int q = 0; q < 4; ++q) hv[q] = fmaf(g[q], v[q], regs.hv[q]);
   Store4<float>::st(e.h + static_cast<int64_t>(m) * e.ldh + n, hv);
 }
 

@@ -29,6 +29,10 @@
 #include "epilogue.h"
 #include "gemm.h"
 
+#ifndef SPECA_EBU
+#define SPECA_EBU EB
+#endif
+
 namespace speca {
 
 namespace {
@@ -121,20 +125,23 @@ __device__ __forceinline__ void tile_epilogue(floatx16 (&acc)[BN / WGN / 32][BM 
       constexpr int EBMAX = (BM / EH > 1) ? 1 : 4;
       constexpr int EB = PASSES % EBMAX == 0 ? EBMAX : (PASSES % 2 == 0 ? 2 : 1);
       if (uniform) {
-        for (int p0 = 0; p0 < PASSES; p0 += EB) {
-          BranchRegs<bf16_t> regs[EB];
+        constexpr int EBU = SPECA_EBU;
+        float g4[4];
+        Store4<float>::ld(br.gate + n, g4);
+        for (int p0 = 0; p0 < PASSES; p0 += EBU) {
+          BranchRegs<bf16_t> regs[EBU];
 #pragma unroll
-          for (int u = 0; u < EB; ++u) {
+          for (int u = 0; u < EBU; ++u) {
             const int r = qr + (p0 + u) * RPP;
             if (mh + r < M) branch_load_u<bf16_t>(epi, br, h * EH + r, mh + r, n, regs[u]);
           }
 #pragma unroll
-          for (int u = 0; u < EB; ++u) {
+          for (int u = 0; u < EBU; ++u) {
             const int r = qr + (p0 + u) * RPP;
             if (mh + r < M) {
               const float4 t = *reinterpret_cast<const float4*>(Cs + r * CST + qc);
               const float v[4] = {t.x + bias[0], t.y + bias[1], t.z + bias[2], t.w + bias[3]};
-              branch_finish_u<bf16_t>(epi, br, h * EH + r, mh + r, n, v, regs[u]);
+              branch_finish_u<bf16_t>(epi, br, h * EH + r, mh + r, n, v, g4, regs[u]);
             }
           }
         }

@@ -16,6 +16,7 @@ struct Profiler {
     double flops, bytes;
   };
   bool on = false;
+  bool keep_lanes = false;   // time the laned schedule as it runs instead of serialising it
   std::vector<Rec> recs;
   std::vector<hipEvent_t> pool;
 

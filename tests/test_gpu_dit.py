@@ -244,3 +244,34 @@ def test_sample_error_paths(tiny):
     with pytest.raises(sp.SpecaError) as e:
         ctx.init_cache(sp.make_cfg(order=1, interval=2, verify_block=5), 2)
     assert e.value.code == bd.EINVAL
+
+
+def test_lanes_do_not_change_results(tiny):
+    """Row groups of a step run side by side on streams of the library; a row's result must not
+    depend on how the rows were grouped: same bits for 1, 2 and 4 lanes (mixed schedule, guided)."""
+    import paper_2509_11628_amd as sp
+    from paper_2509_11628_amd import binding as bd
+    s, w, om, ctx = tiny
+    S, B = 10, 4
+    ts, ab = si.ddim_tables(S)
+    lat = si.make_latents(B, s.in_channels, s.latent_hw, 3)
+    lab = si.make_labels(B, s.num_classes, 3)
+    tau = core.tau_linear(0.08, 0.02, S)
+    outs = []
+    try:
+        for lanes in (1, 2, 4):
+            ctx.set_lanes(lanes)
+            ctx.init_cache(sp.make_cfg(order=2, interval=4), 2 * B)
+            xd = torch.from_numpy(lat).cuda()
+            tr = ctx.sample(xd, ts, ab, tau, cfg_scale=1.5, labels=lab)
+            outs.append((xd.cpu().numpy(), tr))
+    finally:
+        ctx.set_lanes(2)
+    kinds = outs[0][1]["kind"]
+    assert (kinds == 1).any() and (kinds == 0).any()
+    for x, tr in outs[1:]:
+        assert np.array_equal(x, outs[0][0])
+        assert np.array_equal(tr["kind"], kinds) and np.array_equal(tr["err"], outs[0][1]["err"], equal_nan=True)
+    with pytest.raises(sp.SpecaError) as e:
+        ctx.set_lanes(9)
+    assert e.value.code == bd.EINVAL
