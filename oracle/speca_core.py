@@ -76,8 +76,9 @@ def finite_difference_eq3(features_latest_first: Sequence[np.ndarray], i: int) -
 def refresh_divisors(mode: str, step: int, refs_old: Sequence[int], order: int) -> List[float]:
     """Divisor d_i (i = 1..order) of the difference recursion at a new full step
     ``step`` whose previous references are ``refs_old`` (latest first).
-    taylor: the last gap for every i;  newton: the span step - refs_old[i-1]."""
-    if mode == "taylor":
+    taylor: the last gap for every i;  newton: the span step - refs_old[i-1];
+    adams_bashforth: as taylor (the same stored differences, other forecast weights)."""
+    if mode in ("taylor", "adams_bashforth"):
         return [float(step - refs_old[0]) for _ in range(1, order + 1)]
     if mode == "newton":
         return [float(step - refs_old[i - 1]) for i in range(1, order + 1)]
@@ -91,7 +92,7 @@ class FeatureCache:
     ``D[slot][i]`` is the i-th difference; ``refs`` the full steps, latest first."""
 
     def __init__(self, n_slots: int, order: int, mode: str = "taylor", store: Optional[str] = None):
-        assert order >= 0 and mode in ("taylor", "newton")
+        assert order >= 0 and mode in ("taylor", "newton", "adams_bashforth")
         self.n_slots, self.m, self.mode = n_slots, order, mode
         self.round = storage_rounder(store)
         self.D: List[List[Optional[np.ndarray]]] = [[None] * (order + 1) for _ in range(n_slots)]
@@ -139,10 +140,22 @@ def forecast_coefficients(mode: str, step: int, refs: Sequence[int], order: int)
     taylor (Eq. 2 as printed): with k = step - refs[0] and differences already
     divided by the gap, the term Delta^i F (-k)^i / (i! N^i) in the paper's
     decreasing-timestep indexing is  k^i / i!  times the stored i-th difference.
-    newton: prod_{j<i} (step - refs[j])."""
+    newton: prod_{j<i} (step - refs[j]).
+    adams_bashforth (the draft-model ablation of the appendix names the predictor but prints
+    no formula; this is the textbook method in backward-difference form): one explicit
+    Adams step of size h = k from the latest reference,
+        y_{n+1} = y_n + h * sum_{j<q} gamma_j nabla^j f_n,
+    where the derivative samples f_n, f_{n-1}, ... are the successive slopes between
+    references.  The cache holds them as differences: f_n = D^1 and, the stored D^{j+1}
+    being nabla^j f_n divided j times by the last gap g,  nabla^j f_n = g^j D^{j+1}.
+    Hence c_0 = 1 and c_i = k * gamma_{i-1} * g^{i-1}; order q uses q slopes (AB-q)."""
     assert len(refs) >= 1 and order <= len(refs) - 1
     k = step - refs[0]
     assert k > 0
+    if mode == "adams_bashforth":
+        g = float(refs[0] - refs[1]) if len(refs) >= 2 else 1.0
+        gam = adams_bashforth_gammas(order)
+        return [1.0] + [float(k) * gam[i - 1] * g ** (i - 1) for i in range(1, order + 1)]
     if mode == "taylor":
         return [float(k) ** i / math.factorial(i) for i in range(order + 1)]
     if mode == "newton":
@@ -152,6 +165,17 @@ def forecast_coefficients(mode: str, step: int, refs: Sequence[int], order: int)
             p *= float(step - refs[i]) if i < len(refs) else 0.0
         return c
     raise ValueError(mode)
+
+
+def adams_bashforth_gammas(q: int) -> List[float]:
+    """gamma_0 .. gamma_{q-1} of the Adams-Bashforth method in backward-difference form,
+    gamma_j = int_0^1 C(s + j - 1, j) ds, from the classical recurrence
+        gamma_m + gamma_{m-1}/2 + gamma_{m-2}/3 + ... + gamma_0/(m+1) = 1
+    (1, 1/2, 5/12, 3/8, 251/720, ...)."""
+    gam: List[float] = []
+    for m in range(q):
+        gam.append(1.0 - sum(gam[j] / (m - j + 1) for j in range(m)))
+    return gam
 
 
 def taylor_forecast_eq2(features_latest_first: Sequence[np.ndarray], N: int, k: int, m: int) -> np.ndarray:

@@ -232,3 +232,50 @@ def test_bf16_cache_close_to_exact():
         ce.refresh(s, [f]); cb.refresh(s, [f])
     np.testing.assert_array_equal(cb.D[0][0], ce.D[0][0])
     assert np.max(np.abs(cb.forecast(10, 0) - ce.forecast(10, 0))) < 2e-2
+
+
+# ---- Adams-Bashforth draft policy (appendix ablation of draft models; textbook coefficients) -----------------
+
+AB_ORDINATE_WEIGHTS = {   # y_{n+1} = y_n + h sum_j b_j f_{n-j}, classical tables
+    1: [1.0],
+    2: [3 / 2, -1 / 2],
+    3: [23 / 12, -16 / 12, 5 / 12],
+    4: [55 / 24, -59 / 24, 37 / 24, -9 / 24],
+}
+
+
+def test_adams_bashforth_gammas_are_the_classical_ones():
+    np.testing.assert_allclose(core.adams_bashforth_gammas(5), [1, 1 / 2, 5 / 12, 3 / 8, 251 / 720], rtol=1e-14)
+
+
+@pytest.mark.parametrize("q", [1, 2, 3, 4])
+@pytest.mark.parametrize("g,k", [(4, 4), (3, 1), (5, 2)])
+def test_adams_bashforth_equals_ordinate_form(q, g, k):
+    """The forecast from the cached differences equals the method written with its classical
+    weights on the raw slopes between references (uniform gaps g, one step of size k)."""
+    rng = np.random.default_rng(q * 10 + g)
+    steps = [g * i for i in range(q + 1)]                  # q+1 references -> q slopes
+    feats = [rng.standard_normal(7) for _ in steps]
+    cache = core.FeatureCache(1, q, "adams_bashforth")
+    for s_, f in zip(steps, feats):
+        cache.refresh(s_, [f])
+    got = cache.forecast(steps[-1] + k, 0)
+    latest_first = feats[::-1]
+    slopes = [(latest_first[j] - latest_first[j + 1]) / g for j in range(q)]
+    exp = latest_first[0] + k * sum(b * s_ for b, s_ in zip(AB_ORDINATE_WEIGHTS[q], slopes))
+    np.testing.assert_allclose(got, exp, rtol=1e-12, atol=1e-12)
+
+
+def test_adams_bashforth_exact_on_lines_and_differs_from_taylor_on_curves():
+    a, b = 0.7, -0.3
+    cache = core.FeatureCache(1, 2, "adams_bashforth")
+    for u in (0, 4, 8):
+        cache.refresh(u, [np.array([a + b * u])])
+    np.testing.assert_allclose(cache.forecast(11, 0), [a + b * 11], rtol=1e-13)
+    # F(u) = u^2 at u = 0, 4, 8, k = 1: slopes 12 and 4 -> AB2 gives 64 + 1 * (3/2 * 12 - 1/2 * 4) = 80, Eq. 2 gives 77
+    ab = core.FeatureCache(1, 2, "adams_bashforth"); ty = core.FeatureCache(1, 2, "taylor")
+    for u in (0, 4, 8):
+        ab.refresh(u, [np.array([float(u * u)])]); ty.refresh(u, [np.array([float(u * u)])])
+    assert ab.forecast(9, 0)[0] == 80.0 and ty.forecast(9, 0)[0] == 77.0
+    assert core.forecast_coefficients("adams_bashforth", 9, [8, 4, 0], 2) == [1.0, 1.0, 2.0]
+    assert core.forecast_coefficients("adams_bashforth", 9, [8], 0) == [1.0]
