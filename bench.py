@@ -349,6 +349,22 @@ def main():
         "verify_hbm_GBps": cls("verify", PEAK_HBM_GBPS, "bytes", 1e9),
         "other_ms": prof["other"]["ms"],
     }
+    # Speed-up model of the paper's complexity analysis, S = 1 / (1 - alpha (1 - gamma - overhead)), beside
+    # what was measured: alpha from the all-accepted run, gamma = 1 / blocks nominal; the measured cost of an
+    # accepted speculative step relative to a full one (verify block + forecast + everything else) replaces
+    # gamma + overhead in the second prediction.
+    t_full = dt_plain / K
+    n_spec_steps = tr_acc["n_spec"] / float(B)
+    n_full_steps = K - n_spec_steps
+    t_spec = (dt_acc - n_full_steps * t_full) / max(n_spec_steps, 1.0)
+    alpha = n_spec_steps / K
+    gamma = 1.0 / shape.depth
+    extras["speedup_model"] = {
+        "alpha": alpha, "gamma_nominal": gamma, "predicted_nominal": 1.0 / (1.0 - alpha * (1.0 - gamma)),
+        "spec_step_cost_ratio_measured": t_spec / t_full,
+        "predicted_with_measured_cost": 1.0 / (1.0 - alpha * (1.0 - t_spec / t_full)),
+        "measured_vs_plain": dt_plain / dt_acc,
+    }
     out = {
         "metric": "denoising_steps_per_s", "value": K / dt, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
         "ms_per_step": 1e3 * dt / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",

@@ -48,7 +48,7 @@ typedef enum speca_status {
 
 enum { SPECA_F32 = 0, SPECA_BF16 = 1 };                       /* storage types */
 enum { SPECA_MODEL_NONE = 0, SPECA_MODEL_DIT = 1, SPECA_MODEL_MMDIT = 2 };
-enum { SPECA_COEF_TAYLOR = 0, SPECA_COEF_NEWTON = 1 };
+enum { SPECA_COEF_TAYLOR = 0, SPECA_COEF_NEWTON = 1, SPECA_COEF_ADAMS_BASHFORTH = 2 };
 enum { SPECA_SOLVER_DDIM = 0, SPECA_SOLVER_FLOW = 1 };
 enum { SPECA_KIND_FULL = 0, SPECA_KIND_SPEC = 1, SPECA_KIND_REJECT = 2 };
 enum { SPECA_METRIC_L2 = 0, SPECA_METRIC_L1 = 1, SPECA_METRIC_LINF = 2, SPECA_METRIC_COSINE = 3 };
@@ -97,7 +97,7 @@ typedef struct speca_cfg {
   int32_t order;           /* m, 0..SPECA_MAX_ORDER */
   int32_t interval;        /* N >= 1: a full step is forced once step - last_full >= N */
   int32_t verify_block;    /* block recomputed for verification; -1 = last block */
-  int32_t coef_mode;       /* SPECA_COEF_TAYLOR (Eq. 2 as printed) | SPECA_COEF_NEWTON */
+  int32_t coef_mode;       /* SPECA_COEF_TAYLOR (Eq. 2 as printed) | SPECA_COEF_NEWTON | SPECA_COEF_ADAMS_BASHFORTH */
   float   eps;             /* Eq. 4 epsilon, paper value 1e-8 */
   int32_t warmup_full;     /* steps 0..warmup_full-1 are always full (>= 1) */
   int32_t metric;          /* SPECA_METRIC_*; L2 is Eq. 4 */
@@ -258,7 +258,12 @@ int speca_profile_end(speca_ctx* ctx, speca_profile* out);
 int speca_tau_geometric(float tau0, float beta, int steps, float* tau_out);
 /* tau[s] = tau_start + (tau_end - tau_start) * s/(S-1). */
 int speca_tau_linear(float tau_start, float tau_end, int steps, float* tau_out);
-/* Forecast weights c[0..order] for `step` given the references (latest first). */
+/* Forecast weights c[0..order] for `step` given the references (latest first), k = step - refs[0]:
+ *   TAYLOR           c_i = k^i / i!                          (Eq. 2 on differences divided by the last gap)
+ *   NEWTON           c_i = prod_{j<i} (step - refs[j])       (backward divided differences)
+ *   ADAMS_BASHFORTH  c_0 = 1, c_i = k gamma_{i-1} g^{i-1}    (one explicit Adams step of size k on the slopes
+ *                    between references, gamma = 1, 1/2, 5/12, 3/8, g = refs[0] - refs[1]; the draft-model
+ *                    ablation of the appendix names this predictor without a formula: textbook coefficients). */
 int speca_coefficients(int coef_mode, int step, const int32_t* refs, int n_refs, int order, float* c_out);
 /* Refresh divisors d[1..order] written to d_out[0..order-1]. */
 int speca_divisors(int coef_mode, int step, const int32_t* refs, int n_refs, int order, float* d_out);

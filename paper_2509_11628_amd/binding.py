@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libspeca.so")
 OK, EINVAL, ENOMEM, ESTATE, EHIP, EUNSUPPORTED = range(6)
 F32, BF16 = 0, 1
 MODEL_NONE, MODEL_DIT, MODEL_MMDIT = 0, 1, 2
-COEF_TAYLOR, COEF_NEWTON = 0, 1
+COEF_TAYLOR, COEF_NEWTON, COEF_ADAMS_BASHFORTH = 0, 1, 2
 SOLVER_DDIM, SOLVER_FLOW = 0, 1
 KIND_FULL, KIND_SPEC, KIND_REJECT = 0, 1, 2
 METRIC_L2, METRIC_L1, METRIC_LINF, METRIC_COSINE = 0, 1, 2, 3

@@ -92,7 +92,7 @@ static bool cfg_ok(const speca_cfg* c, std::string* why) {
   if (c->order < 0 || c->order > SPECA_MAX_ORDER) { *why = format("order = %d (0..%d)", c->order, SPECA_MAX_ORDER); return false; }
   if (c->interval < 1) { *why = format("interval = %d (>= 1)", c->interval); return false; }
   if (c->warmup_full < 1) { *why = format("warmup_full = %d (>= 1)", c->warmup_full); return false; }
-  if (c->coef_mode != SPECA_COEF_TAYLOR && c->coef_mode != SPECA_COEF_NEWTON) { *why = format("coef_mode = %d", c->coef_mode); return false; }
+  if (c->coef_mode != SPECA_COEF_TAYLOR && c->coef_mode != SPECA_COEF_NEWTON && c->coef_mode != SPECA_COEF_ADAMS_BASHFORTH) { *why = format("coef_mode = %d", c->coef_mode); return false; }
   if (!(c->eps >= 0.0f)) { *why = "eps < 0"; return false; }
   if (c->metric < SPECA_METRIC_L2 || c->metric > SPECA_METRIC_COSINE) { *why = format("metric = %d", c->metric); return false; }
   if (c->verify_block < -1) { *why = format("verify_block = %d", c->verify_block); return false; }

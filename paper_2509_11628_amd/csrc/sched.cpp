@@ -27,6 +27,20 @@ bool forecast_coefficients(int mode, int step, const int32_t* refs, int n_refs, 
     }
     return true;
   }
+  if (mode == SPECA_COEF_ADAMS_BASHFORTH) {
+    // One explicit Adams step of size k in backward-difference form, y + k * sum_j gamma_j nabla^j f,
+    // on the slopes between references; the cache holds nabla^j f / g^j as D^{j+1} (g = last gap).
+    static const double gamma[SPECA_MAX_ORDER] = {1.0, 1.0 / 2.0, 5.0 / 12.0, 3.0 / 8.0};
+    const double g = n_refs >= 2 ? static_cast<double>(refs[0] - refs[1]) : 1.0;
+    if (g <= 0.0) return false;
+    c[0] = 1.0f;
+    double gp = 1.0;
+    for (int i = 1; i <= order; ++i) {
+      c[i] = static_cast<float>(static_cast<double>(k) * gamma[i - 1] * gp);
+      gp *= g;
+    }
+    return true;
+  }
   return false;
 }
 
@@ -35,7 +49,7 @@ bool refresh_divisors(int mode, int step, const int32_t* refs, int n_refs, int o
   if (!refs || !d || order < 0 || order > SPECA_MAX_ORDER || n_refs < order) return false;
   for (int i = 1; i <= order; ++i) {
     int div;
-    if (mode == SPECA_COEF_TAYLOR) div = step - refs[0];
+    if (mode == SPECA_COEF_TAYLOR || mode == SPECA_COEF_ADAMS_BASHFORTH) div = step - refs[0];
     else if (mode == SPECA_COEF_NEWTON) div = step - refs[i - 1];
     else return false;
     if (div <= 0) return false;
@@ -59,7 +73,7 @@ void tau_linear(float a, float b, int steps, float* out) {
 
 static bool cfg_valid(const speca_cfg* c) {
   return c && c->order >= 0 && c->order <= SPECA_MAX_ORDER && c->interval >= 1 && c->warmup_full >= 1 &&
-         (c->coef_mode == SPECA_COEF_TAYLOR || c->coef_mode == SPECA_COEF_NEWTON) && c->eps >= 0.0f &&
+         (c->coef_mode == SPECA_COEF_TAYLOR || c->coef_mode == SPECA_COEF_NEWTON || c->coef_mode == SPECA_COEF_ADAMS_BASHFORTH) && c->eps >= 0.0f &&
          c->metric >= SPECA_METRIC_L2 && c->metric <= SPECA_METRIC_COSINE && c->verify_block >= -1;
 }
 

@@ -53,14 +53,14 @@ CASES = [
 
 
 @pytest.mark.parametrize("slots,B,T,D,dtype", CASES)
-@pytest.mark.parametrize("mode", ["taylor", "newton"])
+@pytest.mark.parametrize("mode", ["taylor", "newton", "adams_bashforth"])
 def test_refresh_forecast_parity(slots, B, T, D, dtype, mode):
     sp = _sp()
     from paper_2509_11628_amd import binding as bd
     m = 2
     dt = bd.BF16 if dtype == "bf16" else bd.F32
     ctx = sp.Context(sp.cache_only_desc(slots, T, D, dt))
-    ctx.init_cache(sp.make_cfg(order=m, interval=100, coef_mode=bd.COEF_NEWTON if mode == "newton" else bd.COEF_TAYLOR), B)
+    ctx.init_cache(sp.make_cfg(order=m, interval=100, coef_mode={"taylor": bd.COEF_TAYLOR, "newton": bd.COEF_NEWTON, "adams_bashforth": bd.COEF_ADAMS_BASHFORTH}[mode]), B)
     oc = _oracle_caches(B, slots, m, mode, dtype)
     # irregular, per-row histories: rows skip some refreshes
     plan = [(0, list(range(B))), (3, list(range(B))), (4, [r for r in range(B) if r % 2 == 0]), (9, list(range(B)))]

@@ -112,7 +112,7 @@ def _run_both(s, om, ctx, S, B, cfg_kwargs, tau, cfg_scale=0.0, seed=0):
     lab = si.make_labels(B, s.num_classes, seed)
     sol = osamp.Solver("ddim", ts, ab, cfg_scale)
     exp, tr = osamp.sample(om, osamp.SpecaConfig(cache_store="bf16" if s.dtype == "bf16" else None, **cfg_kwargs), sol, tau, lat, lab)
-    mode = bd.COEF_NEWTON if cfg_kwargs.get("mode") == "newton" else bd.COEF_TAYLOR
+    mode = {"newton": bd.COEF_NEWTON, "adams_bashforth": bd.COEF_ADAMS_BASHFORTH}.get(cfg_kwargs.get("mode"), bd.COEF_TAYLOR)
     kw = {k: v for k, v in cfg_kwargs.items() if k != "mode"}
     ctx.init_cache(sp.make_cfg(coef_mode=mode, **kw), B * (2 if cfg_scale > 0 else 1))
     xd = torch.from_numpy(lat).cuda()
@@ -180,7 +180,8 @@ def test_config1_trajectory(tiny):
 def test_config1_geometric_and_newton(tiny):
     s, w, om, ctx = tiny
     tau = core.tau_geometric(0.05, 0.2, 20)
-    for kw in (dict(order=1, interval=4), dict(order=2, interval=5, mode="newton"), dict(order=2, interval=5, verify_block=0)):
+    for kw in (dict(order=1, interval=4), dict(order=2, interval=5, mode="newton"), dict(order=2, interval=5, verify_block=0),
+               dict(order=2, interval=5, mode="adams_bashforth"), dict(order=0, interval=3)):
         exp, tr, got, gtr = _run_both(s, om, ctx, 20, 2, kw, tau)
         compared, complete = compare_traces(tr, gtr, s.dtype)
         assert compared >= 6, kw

@@ -38,9 +38,9 @@ def test_struct_layouts_match_header(bd):
     assert bd.MAX_ORDER == 4 and bd.MAX_LAUNCH_ROWS == 64
 
 
-@pytest.mark.parametrize("mode", ["taylor", "newton"])
+@pytest.mark.parametrize("mode", ["taylor", "newton", "adams_bashforth"])
 def test_coefficients_and_divisors_match_oracle(bd, mode):
-    code = bd.COEF_NEWTON if mode == "newton" else bd.COEF_TAYLOR
+    code = {"taylor": bd.COEF_TAYLOR, "newton": bd.COEF_NEWTON, "adams_bashforth": bd.COEF_ADAMS_BASHFORTH}[mode]
     rng = np.random.default_rng(0)
     for _ in range(200):
         n = int(rng.integers(1, 6))
