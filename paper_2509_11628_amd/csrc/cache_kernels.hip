@@ -9,6 +9,8 @@
 // sequence, wave shuffle tree, per-block LDS order, second pass over fixed-size chunk
 // partials), so results are bit-reproducible and do not depend on which other rows share
 // the launch.
+#include <cstdlib>
+
 #include "kernels.h"
 
 namespace speca {
@@ -382,6 +384,44 @@ static Error launch_refresh_nt(const CacheGeom& g, const RowTable& rt, const voi
 Error launch_refresh(const CacheGeom& g, const RowTable& rt, const void* feat, hipStream_t st) {
   if (rt.n <= 0 || rt.n > kMaxRows) SPECA_FAIL(SPECA_EINVAL, "refresh: %d rows in one launch", rt.n);
   return g.dtype == SPECA_BF16 ? launch_refresh_nt<bf16_t>(g, rt, feat, st) : launch_refresh_nt<float>(g, rt, feat, st);
+}
+
+namespace {
+typedef unsigned int warm_u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kWarmPerThread = 4;
+__global__ __launch_bounds__(256) void cache_warm_kernel(CacheGeom g, RowTable rt, int slot, int64_t bytes_per_tensor, int esz) {
+  const int i = blockIdx.y / SPECA_MAX_ORDER, o = blockIdx.y % SPECA_MAX_ORDER;
+  if (o >= rt.order[i]) return;
+  const char* base = static_cast<const char*>(g.base) + g.offset(slot, o, rt.row[i]) * esz;
+  const int64_t first = (static_cast<int64_t>(blockIdx.x) * kWarmPerThread * 256 + threadIdx.x) * 16;
+  warm_u32x4 acc = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int u = 0; u < kWarmPerThread; ++u) {
+    const int64_t off = first + static_cast<int64_t>(u) * 256 * 16;
+    if (off + 16 <= bytes_per_tensor) acc ^= *reinterpret_cast<const warm_u32x4*>(base + off);
+  }
+  asm volatile("" ::"v"(acc));      // the values are not needed, the loads are
+}
+}  // namespace
+
+Error launch_cache_warm(const CacheGeom& g, const RowTable& rt, int slot, hipStream_t st) {
+  if (rt.n <= 0 || rt.n > kMaxRows) SPECA_FAIL(SPECA_EINVAL, "cache warm: %d rows in one launch", rt.n);
+  if (slot < 0 || slot >= g.n_slots) SPECA_FAIL(SPECA_EINVAL, "cache warm: slot %d", slot);
+  int mo = 0;
+  for (int i = 0; i < rt.n; ++i) {
+    if (rt.order[i] < 0 || rt.order[i] > g.m) SPECA_FAIL(SPECA_EINVAL, "cache warm: order %d", rt.order[i]);
+    mo = rt.order[i] > mo ? rt.order[i] : mo;
+  }
+  // SPECA_WARM=0 switches the hint off (A/B timing)
+  static const bool off = [] { const char* e = getenv("SPECA_WARM"); return e && e[0] == '0'; }();
+  if (mo == 0 || off) return ok();                            // first references: nothing old to read
+  const int esz = static_cast<int>(dtype_size(g.dtype));
+  const int64_t bytes = g.E * esz;
+  if (bytes % 16) return ok();                                // only a hint: skip odd geometries
+  dim3 grid(static_cast<unsigned>((bytes + 256 * 16 * kWarmPerThread - 1) / (256 * 16 * kWarmPerThread)), rt.n * SPECA_MAX_ORDER);
+  cache_warm_kernel<<<grid, 256, 0, st>>>(g, rt, slot, bytes, esz);
+  SPECA_HIP(hipGetLastError());
+  return ok();
 }
 
 int verify_chunks(int64_t E) { return static_cast<int>((E + kChunk - 1) / kChunk); }

@@ -201,6 +201,10 @@ struct DiT final : Model {
       ProfScope ps(ctx, st, SPECA_PROF_GEMM, 2.0 * Md * 3 * D * D, (Md * 4 * D + 3.0 * D * D) * esz);
       SPECA_TRY(launch_gemm(d.dtype, xn_l, D, blk[l].qkv_w, D, static_cast<int>(M), 3 * D, D, e, st));
     }
+    if (refresh_rt) {
+      ProfScope ps(ctx, st, SPECA_PROF_REFRESH, 0.0, table_tensors(*refresh_rt) * static_cast<double>(TD) * esz);
+      SPECA_TRY(launch_cache_warm(ctx->geom, *refresh_rt, 2 * l, st));
+    }
     {
       ProfScope ps(ctx, st, SPECA_PROF_ATTENTION, 4.0 * n * H * static_cast<double>(T) * T * hd, Md * 4 * D * esz);
       SPECA_TRY(launch_attention(d.dtype, qkv_l, att_l, D, n, T, H, hd, st));
@@ -226,6 +230,10 @@ struct DiT final : Model {
     {
       ProfScope ps(ctx, st, SPECA_PROF_OTHER, 0.0, Md * D * (4 + esz));
       SPECA_TRY(launch_ln_modulate(d.dtype, hl, mod_at(l, 3, ln.o), mod_at(l, 4, ln.o), mod_n, xn_l, M, T, D, st));
+    }
+    if (refresh_rt && !truth_out) {
+      ProfScope ps(ctx, st, SPECA_PROF_REFRESH, 0.0, table_tensors(*refresh_rt) * static_cast<double>(TD) * esz);
+      SPECA_TRY(launch_cache_warm(ctx->geom, *refresh_rt, 2 * l + 1, st));
     }
     GemmEpi e;
     e.mode = EPI_GELU; e.bias = blk[l].fc1_b; e.out = f1_l; e.ldo = Dm;
