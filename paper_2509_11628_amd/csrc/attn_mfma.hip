@@ -444,10 +444,186 @@ __global__ __launch_bounds__(256) void attention_mfma_short_kernel(const uint16_
   }
 }
 
+// Whole-sequence form for T <= 256: one block of 8 waves per (row, head).  Every key and value of the
+// head is brought into LDS by one wave of loads issued all at once (a single memory round trip, one
+// barrier), each wave then owns 32 queries, holds its complete score row in registers (8 sub-tiles),
+// takes the softmax in one pass (no running maximum, no rescaling of O) and runs the second
+// contraction over all keys.  At 256 tokens the tiled kernels spend their time in per-tile load
+// latency and barriers; this form is bound by one load round trip plus ~90 MFMAs per wave.
+template <int HD>
+__global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_t* __restrict__ qkv, uint16_t* __restrict__ out, int64_t ldo,
+                                                                   int T, int H, float scale_log2e) {
+  constexpr int TMAX = 256;
+  constexpr int HD16 = (HD + 15) / 16 * 16, HD32 = (HD + 31) / 32 * 32;
+  constexpr int KS = HD16 / 16;         // reduction steps of q k^T
+  constexpr int DT = HD32 / 32;         // 32-row tiles of O^T
+  constexpr int KST = HD16 + 8;         // LDS row stride of the keys (elements)
+  constexpr int VST = TMAX + 8;         // LDS row stride of the transposed values
+  constexpr int CH = HD / 8;            // 16-byte chunks per key/value row
+  constexpr int NST = TMAX / 32;        // 32-key sub-tiles
+  constexpr int K_CHUNKS = (TMAX * CH + 511) / 512;
+  static_assert(HD % 8 == 0, "head_dim must be a multiple of 8");
+  static_assert((TMAX / 8) * CH <= 512, "one 8x8 value block per thread");
+  extern __shared__ __align__(16) uint16_t smem[];
+  uint16_t* Ks = smem;                        // [TMAX][KST]
+  uint16_t* Vt = smem + TMAX * KST;           // [HD32][VST]
+
+  const int row = blockIdx.z, head = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int64_t D = static_cast<int64_t>(H) * HD;
+  const uint16_t* base = qkv + static_cast<int64_t>(row) * T * 3 * D + head * HD;
+
+  // all global loads first: keys, one 8x8 value block, the wave's queries
+  uint4 rk[K_CHUNKS], rv[8];
+#pragma unroll
+  for (int c = 0; c < K_CHUNKS; ++c) {
+    const int id = tid + c * 512;
+    const int key = id / CH, dc = id - key * CH;
+    rk[c] = (id < TMAX * CH && key < T) ? *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(key) * 3 * D + D + dc * 8) : make_uint4(0, 0, 0, 0);
+  }
+  const bool v_thread = tid < (TMAX / 8) * CH;
+  const int v_kb = tid / CH, v_dc = tid % CH;   // 8x8 block: keys v_kb*8.., dims v_dc*8..
+  if (v_thread) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int key = v_kb * 8 + i;
+      rv[i] = key < T ? *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(key) * 3 * D + 2 * D + v_dc * 8) : make_uint4(0, 0, 0, 0);
+    }
+  }
+  Frag qf[KS];
+  const int q = wave * 32 + l32;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    const int d = ks * 16 + lhi * 8;
+    qf[ks].u = (q < T && d < HD) ? *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(q) * 3 * D + d) : make_uint4(0, 0, 0, 0);
+  }
+
+  // zero padding: key columns [HD, HD16) and value rows [HD, HD32)
+  if (HD16 > HD)
+    for (int i = tid; i < TMAX * (HD16 - HD); i += 512) Ks[(i / (HD16 - HD)) * KST + HD + i % (HD16 - HD)] = 0;
+  if (HD32 > HD)
+    for (int i = tid; i < (HD32 - HD) * TMAX; i += 512) Vt[(HD + i / TMAX) * VST + i % TMAX] = 0;
+#pragma unroll
+  for (int c = 0; c < K_CHUNKS; ++c) {
+    const int id = tid + c * 512;
+    const int key = id / CH, dc = id - key * CH;
+    if (id < TMAX * CH) *reinterpret_cast<uint4*>(Ks + key * KST + dc * 8) = rk[c];
+  }
+  if (v_thread) {
+    // rv[i] = 8 dims of key i  ->  8 rows (dims) of 8 keys
+    const uint32_t w[8][4] = {{rv[0].x, rv[0].y, rv[0].z, rv[0].w}, {rv[1].x, rv[1].y, rv[1].z, rv[1].w},
+                              {rv[2].x, rv[2].y, rv[2].z, rv[2].w}, {rv[3].x, rv[3].y, rv[3].z, rv[3].w},
+                              {rv[4].x, rv[4].y, rv[4].z, rv[4].w}, {rv[5].x, rv[5].y, rv[5].z, rv[5].w},
+                              {rv[6].x, rv[6].y, rv[6].z, rv[6].w}, {rv[7].x, rv[7].y, rv[7].z, rv[7].w}};
+#pragma unroll
+    for (int dd = 0; dd < 8; ++dd) {
+      uint32_t r[4];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const uint32_t a = w[2 * kk][dd >> 1], b = w[2 * kk + 1][dd >> 1];
+        r[kk] = (dd & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
+      }
+      *reinterpret_cast<uint4*>(Vt + (v_dc * 8 + dd) * VST + v_kb * 8) = make_uint4(r[0], r[1], r[2], r[3]);
+    }
+  }
+  __syncthreads();
+  if (wave * 32 >= T) return;                  // no barrier after this point
+
+  const int nst = (T + 31) / 32;               // sub-tiles that hold keys
+  floatx16 s[NST];
+  float tmax = -INFINITY;
+#pragma unroll
+  for (int st = 0; st < NST; ++st) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s[st][e] = 0.0f;
+    if (st < nst) {
+      const uint16_t* kp = Ks + (st * 32 + l32) * KST + lhi * 8;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        Frag kf;
+        kf.u = *reinterpret_cast<const uint4*>(kp + ks * 16);
+        s[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, s[st], 0, 0, 0);
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int key = st * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
+        const float v = key < T ? s[st][e] * scale_log2e : -INFINITY;
+        s[st][e] = v;
+        tmax = fmaxf(tmax, v);
+      }
+    }
+  }
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+  float psum = 0.0f;
+#pragma unroll
+  for (int st = 0; st < NST; ++st)
+    if (st < nst) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float p = exp2f(s[st][e] - tmax);
+        s[st][e] = p;
+        psum += p;
+      }
+    }
+  floatx16 o[DT];
+#pragma unroll
+  for (int i = 0; i < DT; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[i][e] = 0.0f;
+#pragma unroll
+  for (int t = 0; t < 2 * NST; ++t) {
+    const int st = t >> 1, j0 = (t & 1) * 8;      // accumulator entries j0 .. j0+7 of sub-tile st: 16 keys
+    if (st < nst) {
+      Frag pf;
+      pf.u = make_uint4(cvt_pk_bf16(s[st][j0], s[st][j0 + 1]), cvt_pk_bf16(s[st][j0 + 2], s[st][j0 + 3]),
+                        cvt_pk_bf16(s[st][j0 + 4], s[st][j0 + 5]), cvt_pk_bf16(s[st][j0 + 6], s[st][j0 + 7]));
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        const uint16_t* vp = Vt + (dt * 32 + l32) * VST + t * 16 + 4 * lhi;
+        const uint2 lo = *reinterpret_cast<const uint2*>(vp);
+        const uint2 hi = *reinterpret_cast<const uint2*>(vp + 8);
+        Frag vf;
+        vf.u = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[dt], 0, 0, 0);
+      }
+    }
+  }
+  const float ltot = psum + __shfl_xor(psum, 32, 64);
+  const float inv = 1.0f / ltot;
+  if (q < T) {
+    uint16_t* op = out + (static_cast<int64_t>(row) * T + q) * ldo + head * HD;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int d = dt * 32 + 8 * jj + 4 * lhi;
+        if (d < HD) {
+          uint2 r;
+          r.x = cvt_pk_bf16(o[dt][4 * jj] * inv, o[dt][4 * jj + 1] * inv);
+          r.y = cvt_pk_bf16(o[dt][4 * jj + 2] * inv, o[dt][4 * jj + 3] * inv);
+          *reinterpret_cast<uint2*>(op + d) = r;
+        }
+      }
+  }
+}
+
 template <int HD>
 Error launch_hd(const void* qkv, void* out, int64_t ldo, int rows, int T, int H, hipStream_t st) {
   constexpr int HD16 = (HD + 15) / 16 * 16, HD32 = (HD + 31) / 32 * 32;
   const size_t smem = static_cast<size_t>(2) * (64 * (HD16 + 8) + HD32 * (64 + 8)) * sizeof(uint16_t);
+  if (T <= 256) {
+    constexpr size_t smem_w = (static_cast<size_t>(256) * (HD16 + 8) + static_cast<size_t>(HD32) * (256 + 8)) * sizeof(uint16_t);
+    static bool attr_w = false;
+    if (smem_w > 64 * 1024 && !attr_w) {
+      SPECA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attention_mfma_whole_kernel<HD>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem_w)));
+      attr_w = true;
+    }
+    const float sl2 = 1.4426950408889634f / sqrtf(static_cast<float>(HD));
+    attention_mfma_whole_kernel<HD><<<dim3(1, H, rows), 512, smem_w, st>>>(static_cast<const uint16_t*>(qkv), static_cast<uint16_t*>(out), ldo, T, H, sl2);
+    SPECA_HIP(hipGetLastError());
+    return ok();
+  }
   const bool pipelined = T > 512;      // measured: the pipelined kernel wins from ~8 key tiles on
   auto kern = pipelined ? attention_mfma_kernel<HD> : attention_mfma_short_kernel<HD>;
   static bool attr_set = false;

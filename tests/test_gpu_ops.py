@@ -82,7 +82,8 @@ def test_linear_row_result_independent_of_m():
     assert torch.equal(full[4000:4096], bd.linear(a[4000:4096].contiguous(), w))
 
 
-@pytest.mark.parametrize("rows,T,H,hd", [(2, 16, 4, 16), (1, 100, 2, 72), (2, 256, 3, 72), (1, 77, 2, 64), (1, 300, 2, 128), (1, 64, 1, 32)])
+@pytest.mark.parametrize("rows,T,H,hd", [(2, 16, 4, 16), (1, 100, 2, 72), (2, 256, 3, 72), (1, 77, 2, 64), (1, 300, 2, 128), (1, 64, 1, 32),
+                                          (1, 256, 2, 128), (3, 200, 2, 64), (1, 257, 2, 72), (1, 33, 1, 128)])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_attention(rows, T, H, hd, dtype):
     bd = _bd()
