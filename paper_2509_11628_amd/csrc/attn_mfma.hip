@@ -13,7 +13,7 @@
 // accumulators: the MFMA reduction index is a dummy, so the keys are simply fed to the second
 // MFMA in the order the first one left them in the lane (keys 16t+4h+0..3, 16t+8+4h+0..3 for
 // half-wave h), and V^T is read from LDS in that same order.
-// V is transposed on its way into LDS (8x8 register transposes, 16-byte LDS writes).
+// V is transposed on its way into LDS (8x8 register transposes) into a swizzled, key-permuted layout.
 // The contraction of the next key tile is issued before the softmax of the current one, so the
 // exponentials (quarter-rate on the vector ALUs) overlap with matrix-core work.
 // head_dim is padded with zeros to a multiple of 16 for q k^T and of 32 for P V.
@@ -42,6 +42,35 @@ __device__ inline uint32_t cvt_pk_bf16(float a, float b) {
   return *reinterpret_cast<const uint32_t*>(&r);
 }
 
+// Transposed value tile in LDS: row = head dimension d, NK keys per row, rows unpadded.  The second
+// MFMA wants, per lane and 16-key step t, the keys 16t + 4h + {0..3} and 16t + 8 + 4h + {0..3}
+// (h = lane / 32): the keys of every group of 16 are stored in the order [0-3, 8-11 | 4-7, 12-15], so
+// each half-wave's eight keys are ONE 16-byte chunk (chunk 2t + h) and a fragment is one
+// ds_read_b128.  The chunk position is XOR-swizzled with the row so that the 16 lanes of a read
+// phase (16 consecutive rows, same chunk) cover all 64 banks: with 64-key rows (32 words) the row
+// parity supplies one bank bit and d & 7 the other three; with 256-key rows (a multiple of 64 words)
+// all four come from d & 15.  The higher bits of d are XORed in as well: the transposing writer's
+// lanes hold rows 8 apart (same d & 7), and without them its 8-byte writes would pile 8-deep onto two
+// bank groups; with them they are at most 2-deep (checked by enumeration for head_dim 64 / 128).
+// (Padded rows with two 8-byte reads per fragment measured 58 % of the LDS-active cycles as
+// bank-conflict stalls.)
+template <int NK>
+__device__ inline int vt_swz(int d) {
+  return NK % 128 == 0 ? ((d & 15) ^ ((d >> 4) & 7)) : ((d & 7) ^ ((d >> 3) & 7));
+}
+// element offset of the chunk that holds keys [16t + 4h .. ] u [16t + 8 + 4h ..] of dimension d
+template <int NK>
+__device__ inline int vt_read_off(int d, int t, int h) {
+  return d * NK + (((2 * t + h) ^ vt_swz<NK>(d)) << 3);
+}
+// element offsets where the keys 8kb .. 8kb+3 (lo) and 8kb+4 .. 8kb+7 (hi) of dimension d go (8 bytes each)
+template <int NK>
+__device__ inline void vt_write_off(int d, int kb, int* lo, int* hi) {
+  const int c = 2 * (kb >> 1), half = kb & 1, sw = vt_swz<NK>(d);
+  *lo = d * NK + ((c ^ sw) << 3) + 4 * half;
+  *hi = d * NK + (((c + 1) ^ sw) << 3) + 4 * half;
+}
+
 // Software pipeline (per wave, per 64-key tile k):
 //     issue S(k+1) = K(k+1) q^T          (MFMA, runs in the matrix pipe ...)
 //     softmax of S(k) -> P(k), rescale   (... while the vector ALUs do this)
@@ -56,13 +85,13 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const uint16_t* __r
   constexpr int KS = HD16 / 16;         // reduction steps of q k^T
   constexpr int DT = HD32 / 32;         // 32-row tiles of O^T
   constexpr int KST = HD16 + 8;         // LDS row stride of the key tile (elements)
-  constexpr int VST = 64 + 8;           // LDS row stride of the transposed value tile
+  constexpr int VTILE = HD32 * 64;      // elements of one transposed value tile (see vt_read_off)
   constexpr int CH = HD / 8;            // 16-byte chunks per key/value row
   constexpr int K_CHUNKS = (64 * CH + 255) / 256;
   static_assert(HD % 8 == 0, "head_dim must be a multiple of 8");
   extern __shared__ __align__(16) uint16_t smem[];
   uint16_t* Ks = smem;                        // [2][64][KST]
-  uint16_t* Vt = smem + 2 * 64 * KST;         // [2][HD32][VST]
+  uint16_t* Vt = smem + 2 * 64 * KST;         // [2][VTILE]
 
   const int row = blockIdx.z, head = blockIdx.y, q0 = blockIdx.x * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -76,7 +105,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const uint16_t* __r
   if (HD32 > HD)
     for (int i = tid; i < 2 * (HD32 - HD) * 64; i += 256) {
       const int b = i / ((HD32 - HD) * 64), r = (i / 64) % (HD32 - HD), c = i % 64;
-      Vt[(b * HD32 + HD + r) * VST + c] = 0;
+      Vt[b * VTILE + (HD + r) * 64 + c] = 0;      // whole rows: the order inside a row does not matter
     }
 
   // the wave's 32 queries as B operand, resident in registers
@@ -141,7 +170,10 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const uint16_t* __r
         const uint32_t a_ = rv[2 * kk][dd >> 1], b_ = rv[2 * kk + 1][dd >> 1];                                 \
         r_[kk] = (dd & 1) ? ((a_ >> 16) | (b_ & 0xFFFF0000u)) : ((a_ & 0xFFFFu) | (b_ << 16));                 \
       }                                                                                                        \
-      *reinterpret_cast<u32x4*>(Vt + ((buf) * HD32 + v_dc * 8 + dd) * VST + v_kb * 8) = r_;                    \
+      int lo_, hi_;                                                                                            \
+      vt_write_off<64>(v_dc * 8 + dd, v_kb, &lo_, &hi_);                                                       \
+      *reinterpret_cast<uint2*>(Vt + (buf) * VTILE + lo_) = make_uint2(r_[0], r_[1]);                          \
+      *reinterpret_cast<uint2*>(Vt + (buf) * VTILE + hi_) = make_uint2(r_[2], r_[3]);                          \
     }                                                                                                          \
   }
 #define SPECA_QK(dst, buf)                                                                                     \
@@ -205,11 +237,8 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const uint16_t* __r
       Frag pf;                                                                                                 \
       pf.u = make_uint4(pk[st][j0], pk[st][j0 + 1], pk[st][j0 + 2], pk[st][j0 + 3]);                           \
       _Pragma("unroll") for (int dt = 0; dt < DT; ++dt) {                                                      \
-        const uint16_t* vp = Vt + (buf * HD32 + dt * 32 + l32) * VST + t * 16 + 4 * lhi;                       \
-        const uint2 lo = *reinterpret_cast<const uint2*>(vp);                                                  \
-        const uint2 hi = *reinterpret_cast<const uint2*>(vp + 8);                                              \
         Frag vf;                                                                                               \
-        vf.u = make_uint4(lo.x, lo.y, hi.x, hi.y);                                                             \
+        vf.u = *reinterpret_cast<const uint4*>(Vt + buf * VTILE + vt_read_off<64>(dt * 32 + l32, t, lhi));     \
         o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[dt], 0, 0, 0);                           \
       }                                                                                                        \
     }                                                                                                          \
@@ -264,13 +293,13 @@ __global__ __launch_bounds__(256) void attention_mfma_short_kernel(const uint16_
   constexpr int KS = HD16 / 16;         // reduction steps of q k^T
   constexpr int DT = HD32 / 32;         // 32-row tiles of O^T
   constexpr int KST = HD16 + 8;         // LDS row stride of the key tile (elements)
-  constexpr int VST = 64 + 8;           // LDS row stride of the transposed value tile
+  constexpr int VTILE = HD32 * 64;      // elements of one transposed value tile (see vt_read_off)
   constexpr int CH = HD / 8;            // 16-byte chunks per key/value row
   constexpr int K_CHUNKS = (64 * CH + 255) / 256;
   static_assert(HD % 8 == 0, "head_dim must be a multiple of 8");
   extern __shared__ __align__(16) uint16_t smem[];
   uint16_t* Ks = smem;                        // [2][64][KST]
-  uint16_t* Vt = smem + 2 * 64 * KST;         // [2][HD32][VST]
+  uint16_t* Vt = smem + 2 * 64 * KST;         // [2][VTILE]
 
   const int row = blockIdx.z, head = blockIdx.y, q0 = blockIdx.x * 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -284,7 +313,7 @@ __global__ __launch_bounds__(256) void attention_mfma_short_kernel(const uint16_
   if (HD32 > HD)
     for (int i = tid; i < 2 * (HD32 - HD) * 64; i += 256) {
       const int b = i / ((HD32 - HD) * 64), r = (i / 64) % (HD32 - HD), c = i % 64;
-      Vt[(b * HD32 + HD + r) * VST + c] = 0;
+      Vt[b * VTILE + (HD + r) * 64 + c] = 0;      // whole rows: the order inside a row does not matter
     }
 
   // the wave's 32 queries as B operand, resident in registers
@@ -345,7 +374,10 @@ __global__ __launch_bounds__(256) void attention_mfma_short_kernel(const uint16_
           const uint32_t a = w[2 * kk][dd >> 1], b = w[2 * kk + 1][dd >> 1];
           r[kk] = (dd & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
         }
-        *reinterpret_cast<uint4*>(Vt + (buf * HD32 + v_dc * 8 + dd) * VST + v_kb * 8) = make_uint4(r[0], r[1], r[2], r[3]);
+        int lo_, hi_;
+        vt_write_off<64>(v_dc * 8 + dd, v_kb, &lo_, &hi_);
+        *reinterpret_cast<uint2*>(Vt + buf * VTILE + lo_) = make_uint2(r[0], r[1]);
+        *reinterpret_cast<uint2*>(Vt + buf * VTILE + hi_) = make_uint2(r[2], r[3]);
       }
     }
   };
@@ -412,11 +444,8 @@ __global__ __launch_bounds__(256) void attention_mfma_short_kernel(const uint16_
                         pack_bf16(s[st][j0 + 4], s[st][j0 + 5]), pack_bf16(s[st][j0 + 6], s[st][j0 + 7]));
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
-        const uint16_t* vp = Vt + (buf * HD32 + dt * 32 + l32) * VST + t * 16 + 4 * lhi;
-        const uint2 lo = *reinterpret_cast<const uint2*>(vp);
-        const uint2 hi = *reinterpret_cast<const uint2*>(vp + 8);
         Frag vf;
-        vf.u = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        vf.u = *reinterpret_cast<const uint4*>(Vt + buf * VTILE + vt_read_off<64>(dt * 32 + l32, t, lhi));
         o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[dt], 0, 0, 0);
       }
     }
@@ -458,7 +487,6 @@ __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_
   constexpr int KS = HD16 / 16;         // reduction steps of q k^T
   constexpr int DT = HD32 / 32;         // 32-row tiles of O^T
   constexpr int KST = HD16 + 8;         // LDS row stride of the keys (elements)
-  constexpr int VST = TMAX + 8;         // LDS row stride of the transposed values
   constexpr int CH = HD / 8;            // 16-byte chunks per key/value row
   constexpr int NST = TMAX / 32;        // 32-key sub-tiles
   constexpr int K_CHUNKS = (TMAX * CH + 511) / 512;
@@ -466,7 +494,7 @@ __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_
   static_assert((TMAX / 8) * CH <= 512, "one 8x8 value block per thread");
   extern __shared__ __align__(16) uint16_t smem[];
   uint16_t* Ks = smem;                        // [TMAX][KST]
-  uint16_t* Vt = smem + TMAX * KST;           // [HD32][VST]
+  uint16_t* Vt = smem + TMAX * KST;           // [HD32][TMAX], see vt_read_off
 
   const int row = blockIdx.z, head = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -503,7 +531,7 @@ __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_
   if (HD16 > HD)
     for (int i = tid; i < TMAX * (HD16 - HD); i += 512) Ks[(i / (HD16 - HD)) * KST + HD + i % (HD16 - HD)] = 0;
   if (HD32 > HD)
-    for (int i = tid; i < (HD32 - HD) * TMAX; i += 512) Vt[(HD + i / TMAX) * VST + i % TMAX] = 0;
+    for (int i = tid; i < (HD32 - HD) * TMAX; i += 512) Vt[HD * TMAX + i] = 0;
 #pragma unroll
   for (int c = 0; c < K_CHUNKS; ++c) {
     const int id = tid + c * 512;
@@ -524,7 +552,10 @@ __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_
         const uint32_t a = w[2 * kk][dd >> 1], b = w[2 * kk + 1][dd >> 1];
         r[kk] = (dd & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
       }
-      *reinterpret_cast<uint4*>(Vt + (v_dc * 8 + dd) * VST + v_kb * 8) = make_uint4(r[0], r[1], r[2], r[3]);
+      int lo_, hi_;
+      vt_write_off<TMAX>(v_dc * 8 + dd, v_kb, &lo_, &hi_);
+      *reinterpret_cast<uint2*>(Vt + lo_) = make_uint2(r[0], r[1]);
+      *reinterpret_cast<uint2*>(Vt + hi_) = make_uint2(r[2], r[3]);
     }
   }
   __syncthreads();
@@ -580,11 +611,8 @@ __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_
                         cvt_pk_bf16(s[st][j0 + 4], s[st][j0 + 5]), cvt_pk_bf16(s[st][j0 + 6], s[st][j0 + 7]));
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
-        const uint16_t* vp = Vt + (dt * 32 + l32) * VST + t * 16 + 4 * lhi;
-        const uint2 lo = *reinterpret_cast<const uint2*>(vp);
-        const uint2 hi = *reinterpret_cast<const uint2*>(vp + 8);
         Frag vf;
-        vf.u = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        vf.u = *reinterpret_cast<const uint4*>(Vt + vt_read_off<TMAX>(dt * 32 + l32, t, lhi));
         o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[dt], 0, 0, 0);
       }
     }
@@ -611,9 +639,9 @@ __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_
 template <int HD>
 Error launch_hd(const void* qkv, void* out, int64_t ldo, int rows, int T, int H, hipStream_t st) {
   constexpr int HD16 = (HD + 15) / 16 * 16, HD32 = (HD + 31) / 32 * 32;
-  const size_t smem = static_cast<size_t>(2) * (64 * (HD16 + 8) + HD32 * (64 + 8)) * sizeof(uint16_t);
+  const size_t smem = static_cast<size_t>(2) * (64 * (HD16 + 8) + HD32 * 64) * sizeof(uint16_t);
   if (T <= 256) {
-    constexpr size_t smem_w = (static_cast<size_t>(256) * (HD16 + 8) + static_cast<size_t>(HD32) * (256 + 8)) * sizeof(uint16_t);
+    constexpr size_t smem_w = (static_cast<size_t>(256) * (HD16 + 8) + static_cast<size_t>(HD32) * 256) * sizeof(uint16_t);
     static bool attr_w = false;
     if (smem_w > 64 * 1024 && !attr_w) {
       SPECA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attention_mfma_whole_kernel<HD>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem_w)));
