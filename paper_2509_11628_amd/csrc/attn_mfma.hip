@@ -42,6 +42,10 @@ __device__ inline uint32_t cvt_pk_bf16(float a, float b) {
   return *reinterpret_cast<const uint32_t*>(&r);
 }
 
+// 2^x by the hardware instruction alone (inputs are <= 0 here; results below the normal range flush
+// to 0, -inf gives 0): exp2f() wraps it in range checks and a rescale, ~5 vector instructions per value.
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // Transposed value tile in LDS: row = head dimension d, NK keys per row, rows unpadded.  The second
 // MFMA wants, per lane and 16-key step t, the keys 16t + 4h + {0..3} and 16t + 8 + 4h + {0..3}
 // (h = lane / 32): the keys of every group of 16 are stored in the order [0-3, 8-11 | 4-7, 12-15], so
@@ -130,9 +134,13 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const uint16_t* __r
   const int last_key = T - 1;
   // branch-free staging: keys beyond T re-read the last key (their scores are masked, their
   // probabilities are exactly 0, so the duplicated value rows contribute nothing)
-  u32x4 rk[K_CHUNKS], rv[8];
-  const bool v_thread = tid < 8 * CH;
-  const int v_kb = (tid / CH) & 7, v_dc = tid % CH;   // 8x8 block: keys v_kb*8.., dims v_dc*8..
+  // values: every thread (of the first 16 * CH) stages a block of 4 keys x 8 dims: 4 loads, one 8-byte
+  // transposed write per dim.  The 4-key blocks are numbered so that the two blocks a 32-lane write
+  // phase touches differ in the half of the 16-byte chunk they fill (2-deep bank conflicts at most).
+  u32x4 rk[K_CHUNKS], rv[4];
+  const bool v_thread = tid < 16 * CH;
+  const int v_a = (tid / CH) & 15, v_dc = tid % CH;
+  const int v_k4 = (v_a & ~3) | ((v_a & 1) << 1) | ((v_a >> 1) & 1);     // keys v_k4*4 .. +3, dims v_dc*8 .. +7
 #define SPECA_LOADK(kt_)                                                                                        \
   {                                                                                                            \
     const int k0_ = ((kt_) < ntiles ? (kt_) : ntiles - 1) * 64;                                                \
@@ -147,8 +155,8 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const uint16_t* __r
 #define SPECA_LOADV(kt_)                                                                                        \
   {                                                                                                            \
     const int k0_ = ((kt_) < ntiles ? (kt_) : ntiles - 1) * 64;                                                \
-    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                            \
-      const int key_ = k0_ + v_kb * 8 + i;                                                                     \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                            \
+      const int key_ = k0_ + v_k4 * 4 + i;                                                                     \
       const int kk_ = key_ < T ? key_ : last_key;                                                              \
       rv[i] = *reinterpret_cast<const u32x4*>(base + static_cast<int64_t>(kk_) * 3 * D + 2 * D + v_dc * 8);    \
     }                                                                                                          \
@@ -161,19 +169,18 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const uint16_t* __r
       if (id < 64 * CH) *reinterpret_cast<u32x4*>(Ks + ((buf) * 64 + key_) * KST + dc_ * 8) = rk[c];           \
     }                                                                                                          \
   }
-  // rv[i] = 8 dims of key i  ->  8 rows (dims) of 8 keys
+  // rv[i] = 8 dims of key i  ->  8 rows (dims) of 4 keys
 #define SPECA_STOREV(buf)                                                                                      \
   if (v_thread) {                                                                                              \
+    const int c_ = 2 * (v_k4 >> 2) + (v_k4 & 1), h_ = (v_k4 >> 1) & 1;                                         \
     _Pragma("unroll") for (int dd = 0; dd < 8; ++dd) {                                                         \
-      u32x4 r_;                                                                                                \
-      _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                                       \
+      const int d_ = v_dc * 8 + dd;                                                                            \
+      uint32_t r_[2];                                                                                          \
+      _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                                                       \
         const uint32_t a_ = rv[2 * kk][dd >> 1], b_ = rv[2 * kk + 1][dd >> 1];                                 \
         r_[kk] = (dd & 1) ? ((a_ >> 16) | (b_ & 0xFFFF0000u)) : ((a_ & 0xFFFFu) | (b_ << 16));                 \
       }                                                                                                        \
-      int lo_, hi_;                                                                                            \
-      vt_write_off<64>(v_dc * 8 + dd, v_kb, &lo_, &hi_);                                                       \
-      *reinterpret_cast<uint2*>(Vt + (buf) * VTILE + lo_) = make_uint2(r_[0], r_[1]);                          \
-      *reinterpret_cast<uint2*>(Vt + (buf) * VTILE + hi_) = make_uint2(r_[2], r_[3]);                          \
+      *reinterpret_cast<uint2*>(Vt + (buf) * VTILE + d_ * 64 + ((c_ ^ vt_swz<64>(d_)) << 3) + 4 * h_) = make_uint2(r_[0], r_[1]); \
     }                                                                                                          \
   }
 #define SPECA_QK(dst, buf)                                                                                     \
@@ -218,24 +225,23 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const uint16_t* __r
     const float mnew = fmaxf(mrun, tmax);                                                                      \
     const float moff = mnew * scale_log2e;                                                                     \
     float psum = 0.0f;                                                                                         \
-    uint32_t pk[2][8];                                                                                         \
-    _Pragma("unroll") for (int st = 0; st < 2; ++st) _Pragma("unroll") for (int q = 0; q < 16; q += 2) {       \
-      const float p0 = exp2f(fmaf(CUR[st][q], scale_log2e, -moff));                                            \
-      const float p1 = exp2f(fmaf(CUR[st][q + 1], scale_log2e, -moff));                                        \
-      psum += p0 + p1;                                                                                         \
-      pk[st][q >> 1] = cvt_pk_bf16(p0, p1);                                                                    \
+    _Pragma("unroll") for (int st = 0; st < 2; ++st) _Pragma("unroll") for (int q = 0; q < 16; ++q) {          \
+      const float p = fast_exp2(fmaf(CUR[st][q], scale_log2e, -moff));                                         \
+      CUR[st][q] = p;                                                                                          \
+      psum += p;                                                                                               \
     }                                                                                                          \
     if (__any(mnew != mrun)) {       /* the running maximum moved somewhere in the wave: rescale */            \
-      const float corr = exp2f(mrun * scale_log2e - moff);                                                     \
+      const float corr = fast_exp2(mrun * scale_log2e - moff);                                                 \
       lrun *= corr;                                                                                            \
       _Pragma("unroll") for (int i = 0; i < DT; ++i) _Pragma("unroll") for (int q = 0; q < 16; ++q) o[i][q] *= corr; \
       mrun = mnew;                                                                                             \
     }                                                                                                          \
     lrun += psum;                                                                                              \
     _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                            \
-      const int st = t >> 1, j0 = (t & 1) * 4;                                                                 \
-      Frag pf;                                                                                                 \
-      pf.u = make_uint4(pk[st][j0], pk[st][j0 + 1], pk[st][j0 + 2], pk[st][j0 + 3]);                           \
+      const int st = t >> 1, j0 = (t & 1) * 8;                                                                 \
+      Frag pf;       /* converted right before use: the packed copy of the whole tile need not stay live */     \
+      pf.u = make_uint4(cvt_pk_bf16(CUR[st][j0], CUR[st][j0 + 1]), cvt_pk_bf16(CUR[st][j0 + 2], CUR[st][j0 + 3]),   \
+                        cvt_pk_bf16(CUR[st][j0 + 4], CUR[st][j0 + 5]), cvt_pk_bf16(CUR[st][j0 + 6], CUR[st][j0 + 7])); \
       _Pragma("unroll") for (int dt = 0; dt < DT; ++dt) {                                                      \
         Frag vf;                                                                                               \
         vf.u = *reinterpret_cast<const uint4*>(Vt + buf * VTILE + vt_read_off<64>(dt * 32 + l32, t, lhi));     \
@@ -418,14 +424,14 @@ __global__ __launch_bounds__(256) void attention_mfma_short_kernel(const uint16_
       }
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
     const float mnew = fmaxf(mrun, tmax);
-    const float corr = exp2f(mrun - mnew);
+    const float corr = fast_exp2(mrun - mnew);
     mrun = mnew;
     float psum = 0.0f;
 #pragma unroll
     for (int st = 0; st < 2; ++st)
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
-        const float p = exp2f(s[st][q] - mnew);
+        const float p = fast_exp2(s[st][q] - mnew);
         s[st][q] = p;
         psum += p;
       }
@@ -592,7 +598,7 @@ __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_
     if (st < nst) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const float p = exp2f(s[st][e] - tmax);
+        const float p = fast_exp2(s[st][e] - tmax);
         s[st][e] = p;
         psum += p;
       }
