@@ -13,9 +13,10 @@
 // accumulators: the MFMA reduction index is a dummy, so the keys are simply fed to the second
 // MFMA in the order the first one left them in the lane (keys 16t+4h+0..3, 16t+8+4h+0..3 for
 // half-wave h), and V^T is read from LDS in that same order.
-// V is transposed on its way into LDS (8x8 register transposes) into a swizzled, key-permuted layout.
-// The contraction of the next key tile is issued before the softmax of the current one, so the
-// exponentials (quarter-rate on the vector ALUs) overlap with matrix-core work.
+// V is transposed on its way into LDS (register transposes of 4-key x 8-dim blocks) into a swizzled,
+// key-permuted layout.
+// Two kernels: a tiled one (keys/values in 64-key tiles, online softmax) and, for T <= 256, one that
+// holds the whole sequence of a head in LDS and takes the softmax in one pass.
 // head_dim is padded with zeros to a multiple of 16 for q k^T and of 32 for P V.
 #include "gemm.h"
 
@@ -75,225 +76,14 @@ __device__ inline void vt_write_off(int d, int kb, int* lo, int* hi) {
   *hi = d * NK + (((c + 1) ^ sw) << 3) + 4 * half;
 }
 
-// Software pipeline (per wave, per 64-key tile k):
-//     issue S(k+1) = K(k+1) q^T          (MFMA, runs in the matrix pipe ...)
-//     softmax of S(k) -> P(k), rescale   (... while the vector ALUs do this)
-//     O += V(k)^T P(k)^T                 (MFMA)
-// so the exponentials and the conversions of tile k hide behind the contraction of tile k+1.
-// LDS holds K(k+1) and V(k) at the same time: the key tiles run one tile ahead of the value
-// tiles (both double buffered); two further tiles are in flight in registers.
+// Tiled kernel (T > 256): per 64-key tile, load the next tile into registers, compute the current one
+// from LDS (S^T, softmax, O^T), store the next tile to LDS, one barrier.  Registers are capped so that
+// two blocks share a CU (two waves per SIMD): the exponentials and conversions of one wave overlap
+// the MFMAs of the other.  A software-pipelined variant that issued S of tile k+1 before the softmax
+// of tile k needed > 256 registers (one wave per SIMD, accumulators shuttled through AGPRs: 190
+// register moves per tile) and measured 455 / 596 TFLOP/s at 4608 / 27 286 tokens against 565 / 741.
 template <int HD>
-__global__ __launch_bounds__(256) void attention_mfma_kernel(const uint16_t* __restrict__ qkv, uint16_t* __restrict__ out, int64_t ldo,
-                                                             int T, int H, float scale_log2e) {
-  constexpr int HD16 = (HD + 15) / 16 * 16, HD32 = (HD + 31) / 32 * 32;
-  constexpr int KS = HD16 / 16;         // reduction steps of q k^T
-  constexpr int DT = HD32 / 32;         // 32-row tiles of O^T
-  constexpr int KST = HD16 + 8;         // LDS row stride of the key tile (elements)
-  constexpr int VTILE = HD32 * 64;      // elements of one transposed value tile (see vt_read_off)
-  constexpr int CH = HD / 8;            // 16-byte chunks per key/value row
-  constexpr int K_CHUNKS = (64 * CH + 255) / 256;
-  static_assert(HD % 8 == 0, "head_dim must be a multiple of 8");
-  extern __shared__ __align__(16) uint16_t smem[];
-  uint16_t* Ks = smem;                        // [2][64][KST]
-  uint16_t* Vt = smem + 2 * 64 * KST;         // [2][VTILE]
-
-  const int row = blockIdx.z, head = blockIdx.y, q0 = blockIdx.x * 128;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l32 = lane & 31, lhi = lane >> 5;
-  const int64_t D = static_cast<int64_t>(H) * HD;
-  const uint16_t* base = qkv + static_cast<int64_t>(row) * T * 3 * D + head * HD;
-
-  // zero padding of both buffers: key columns [HD, HD16) and value rows [HD, HD32); never overwritten
-  if (HD16 > HD)
-    for (int i = tid; i < 2 * 64 * (HD16 - HD); i += 256) Ks[(i / (HD16 - HD)) * KST + HD + i % (HD16 - HD)] = 0;
-  if (HD32 > HD)
-    for (int i = tid; i < 2 * (HD32 - HD) * 64; i += 256) {
-      const int b = i / ((HD32 - HD) * 64), r = (i / 64) % (HD32 - HD), c = i % 64;
-      Vt[b * VTILE + (HD + r) * 64 + c] = 0;      // whole rows: the order inside a row does not matter
-    }
-
-  // the wave's 32 queries as B operand, resident in registers
-  Frag qf[KS];
-  {
-    const int q = q0 + wave * 32 + l32;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const int d = ks * 16 + lhi * 8;
-      qf[ks].u = (q < T && d < HD) ? *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(q) * 3 * D + d) : make_uint4(0, 0, 0, 0);
-    }
-  }
-
-  floatx16 o[DT];
-#pragma unroll
-  for (int i = 0; i < DT; ++i)
-#pragma unroll
-    for (int q = 0; q < 16; ++q) o[i][q] = 0.0f;
-  float mrun = -INFINITY, lrun = 0.0f;     // running max of the raw scores and this lane's partial sum
-
-  const int ntiles = (T + 63) / 64;
-  const int last_key = T - 1;
-  // branch-free staging: keys beyond T re-read the last key (their scores are masked, their
-  // probabilities are exactly 0, so the duplicated value rows contribute nothing)
-  // values: every thread (of the first 16 * CH) stages a block of 4 keys x 8 dims: 4 loads, one 8-byte
-  // transposed write per dim.  The 4-key blocks are numbered so that the two blocks a 32-lane write
-  // phase touches differ in the half of the 16-byte chunk they fill (2-deep bank conflicts at most).
-  u32x4 rk[K_CHUNKS], rv[4];
-  const bool v_thread = tid < 16 * CH;
-  const int v_a = (tid / CH) & 15, v_dc = tid % CH;
-  const int v_k4 = (v_a & ~3) | ((v_a & 1) << 1) | ((v_a >> 1) & 1);     // keys v_k4*4 .. +3, dims v_dc*8 .. +7
-#define SPECA_LOADK(kt_)                                                                                        \
-  {                                                                                                            \
-    const int k0_ = ((kt_) < ntiles ? (kt_) : ntiles - 1) * 64;                                                \
-    _Pragma("unroll") for (int c = 0; c < K_CHUNKS; ++c) {                                                     \
-      const int id = tid + c * 256;                                                                            \
-      const int idc = id < 64 * CH ? id : 64 * CH - 1;                                                         \
-      const int key_ = idc / CH, dc_ = idc - key_ * CH;                                                        \
-      const int kk_ = k0_ + key_ < T ? k0_ + key_ : last_key;                                                  \
-      rk[c] = *reinterpret_cast<const u32x4*>(base + static_cast<int64_t>(kk_) * 3 * D + D + dc_ * 8);         \
-    }                                                                                                          \
-  }
-#define SPECA_LOADV(kt_)                                                                                        \
-  {                                                                                                            \
-    const int k0_ = ((kt_) < ntiles ? (kt_) : ntiles - 1) * 64;                                                \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                            \
-      const int key_ = k0_ + v_k4 * 4 + i;                                                                     \
-      const int kk_ = key_ < T ? key_ : last_key;                                                              \
-      rv[i] = *reinterpret_cast<const u32x4*>(base + static_cast<int64_t>(kk_) * 3 * D + 2 * D + v_dc * 8);    \
-    }                                                                                                          \
-  }
-#define SPECA_STOREK(buf)                                                                                      \
-  {                                                                                                            \
-    _Pragma("unroll") for (int c = 0; c < K_CHUNKS; ++c) {                                                     \
-      const int id = tid + c * 256;                                                                            \
-      const int key_ = id / CH, dc_ = id - key_ * CH;                                                          \
-      if (id < 64 * CH) *reinterpret_cast<u32x4*>(Ks + ((buf) * 64 + key_) * KST + dc_ * 8) = rk[c];           \
-    }                                                                                                          \
-  }
-  // rv[i] = 8 dims of key i  ->  8 rows (dims) of 4 keys
-#define SPECA_STOREV(buf)                                                                                      \
-  if (v_thread) {                                                                                              \
-    const int c_ = 2 * (v_k4 >> 2) + (v_k4 & 1), h_ = (v_k4 >> 1) & 1;                                         \
-    _Pragma("unroll") for (int dd = 0; dd < 8; ++dd) {                                                         \
-      const int d_ = v_dc * 8 + dd;                                                                            \
-      uint32_t r_[2];                                                                                          \
-      _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                                                       \
-        const uint32_t a_ = rv[2 * kk][dd >> 1], b_ = rv[2 * kk + 1][dd >> 1];                                 \
-        r_[kk] = (dd & 1) ? ((a_ >> 16) | (b_ & 0xFFFF0000u)) : ((a_ & 0xFFFFu) | (b_ << 16));                 \
-      }                                                                                                        \
-      *reinterpret_cast<uint2*>(Vt + (buf) * VTILE + d_ * 64 + ((c_ ^ vt_swz<64>(d_)) << 3) + 4 * h_) = make_uint2(r_[0], r_[1]); \
-    }                                                                                                          \
-  }
-#define SPECA_QK(dst, buf)                                                                                     \
-  {                                                                                                            \
-    _Pragma("unroll") for (int st = 0; st < 2; ++st) {                                                         \
-      _Pragma("unroll") for (int q = 0; q < 16; ++q) dst[st][q] = 0.0f;                                        \
-      const uint16_t* kp = Ks + ((buf) * 64 + st * 32 + l32) * KST + lhi * 8;                                  \
-      Frag kf[KS];              /* all key fragments of the sub-tile first: one LDS latency, not KS */          \
-      _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) kf[ks].u = *reinterpret_cast<const uint4*>(kp + ks * 16); \
-      _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                                        \
-        dst[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks].v, qf[ks].v, dst[st], 0, 0, 0);               \
-    }                                                                                                          \
-  }
-
-  floatx16 sa[2], sb[2];
-  SPECA_LOADK(0);
-  SPECA_LOADV(0);
-  SPECA_STOREK(0);
-  SPECA_STOREV(0);
-  SPECA_LOADK(1);
-  SPECA_STOREK(1);
-  SPECA_LOADK(2);
-  SPECA_LOADV(1);
-  __syncthreads();
-  SPECA_QK(sa, 0);
-
-  // one pipeline stage; CUR holds the scores of tile kt, NXT receives those of tile kt+1
-#define SPECA_STAGE(CUR, NXT, kt)                                                                              \
-  {                                                                                                            \
-    const int buf = (kt) & 1;                                                                                  \
-    if ((kt) + 1 < ntiles) SPECA_QK(NXT, buf ^ 1);                                                             \
-    const int kbase = (kt) * 64;                                                                               \
-    if (kbase + 64 > T) {                                                                                      \
-      _Pragma("unroll") for (int st = 0; st < 2; ++st) _Pragma("unroll") for (int q = 0; q < 16; ++q) {        \
-        const int key = kbase + st * 32 + 8 * (q >> 2) + 4 * lhi + (q & 3);                                    \
-        if (key >= T) CUR[st][q] = -INFINITY;                                                                  \
-      }                                                                                                        \
-    }                                                                                                          \
-    float tmax = -INFINITY;                                                                                    \
-    _Pragma("unroll") for (int st = 0; st < 2; ++st) _Pragma("unroll") for (int q = 0; q < 16; ++q) tmax = fmaxf(tmax, CUR[st][q]); \
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));                                                              \
-    const float mnew = fmaxf(mrun, tmax);                                                                      \
-    const float moff = mnew * scale_log2e;                                                                     \
-    float psum = 0.0f;                                                                                         \
-    _Pragma("unroll") for (int st = 0; st < 2; ++st) _Pragma("unroll") for (int q = 0; q < 16; ++q) {          \
-      const float p = fast_exp2(fmaf(CUR[st][q], scale_log2e, -moff));                                         \
-      CUR[st][q] = p;                                                                                          \
-      psum += p;                                                                                               \
-    }                                                                                                          \
-    if (__any(mnew != mrun)) {       /* the running maximum moved somewhere in the wave: rescale */            \
-      const float corr = fast_exp2(mrun * scale_log2e - moff);                                                 \
-      lrun *= corr;                                                                                            \
-      _Pragma("unroll") for (int i = 0; i < DT; ++i) _Pragma("unroll") for (int q = 0; q < 16; ++q) o[i][q] *= corr; \
-      mrun = mnew;                                                                                             \
-    }                                                                                                          \
-    lrun += psum;                                                                                              \
-    _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                            \
-      const int st = t >> 1, j0 = (t & 1) * 8;                                                                 \
-      Frag pf;       /* converted right before use: the packed copy of the whole tile need not stay live */     \
-      pf.u = make_uint4(cvt_pk_bf16(CUR[st][j0], CUR[st][j0 + 1]), cvt_pk_bf16(CUR[st][j0 + 2], CUR[st][j0 + 3]),   \
-                        cvt_pk_bf16(CUR[st][j0 + 4], CUR[st][j0 + 5]), cvt_pk_bf16(CUR[st][j0 + 6], CUR[st][j0 + 7])); \
-      _Pragma("unroll") for (int dt = 0; dt < DT; ++dt) {                                                      \
-        Frag vf;                                                                                               \
-        vf.u = *reinterpret_cast<const uint4*>(Vt + buf * VTILE + vt_read_off<64>(dt * 32 + l32, t, lhi));     \
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[dt], 0, 0, 0);                           \
-      }                                                                                                        \
-    }                                                                                                          \
-    SPECA_STOREK(buf);            /* K(kt+2) replaces K(kt), consumed one stage ago */                          \
-    SPECA_STOREV(buf ^ 1);        /* V(kt+1) replaces V(kt-1) */                                                \
-    SPECA_LOADK((kt) + 3);                                                                                     \
-    SPECA_LOADV((kt) + 2);                                                                                     \
-    __syncthreads();                                                                                           \
-  }
-
-  for (int kt = 0; kt < ntiles; kt += 2) {
-    SPECA_STAGE(sa, sb, kt);
-    if (kt + 1 < ntiles) SPECA_STAGE(sb, sa, kt + 1);
-  }
-#undef SPECA_STAGE
-#undef SPECA_QK
-#undef SPECA_STOREV
-#undef SPECA_STOREK
-#undef SPECA_LOADV
-#undef SPECA_LOADK
-
-  const float ltot = lrun + __shfl_xor(lrun, 32, 64);
-  const float inv = 1.0f / ltot;
-  const int q = q0 + wave * 32 + l32;
-  if (q < T) {
-    uint16_t* op = out + (static_cast<int64_t>(row) * T + q) * ldo + head * HD;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int d = dt * 32 + 8 * jj + 4 * lhi;
-        if (d < HD) {
-          uint2 r;
-          r.x = cvt_pk_bf16(o[dt][4 * jj] * inv, o[dt][4 * jj + 1] * inv);
-          r.y = cvt_pk_bf16(o[dt][4 * jj + 2] * inv, o[dt][4 * jj + 3] * inv);
-          *reinterpret_cast<uint2*>(op + d) = r;
-        }
-      }
-  }
-}
-
-__device__ inline uint32_t pack_bf16(float a, float b) {
-  return static_cast<uint32_t>(f32_to_bf16(a)) | (static_cast<uint32_t>(f32_to_bf16(b)) << 16);
-}
-
-// Plain two-stage form (load next tile, compute current) without the cross-tile software
-// pipeline: shorter prologue, faster when the sequence is only a few key tiles long.
-template <int HD>
-__global__ __launch_bounds__(256) void attention_mfma_short_kernel(const uint16_t* __restrict__ qkv, uint16_t* __restrict__ out, int64_t ldo,
+__global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const uint16_t* __restrict__ qkv, uint16_t* __restrict__ out, int64_t ldo,
                                                              int T, int H, float scale_log2e) {
   constexpr int HD16 = (HD + 15) / 16 * 16, HD32 = (HD + 31) / 32 * 32;
   constexpr int KS = HD16 / 16;         // reduction steps of q k^T
@@ -340,9 +130,12 @@ __global__ __launch_bounds__(256) void attention_mfma_short_kernel(const uint16_
     for (int q = 0; q < 16; ++q) o[i][q] = 0.0f;
   float mrun = -INFINITY, lrun = 0.0f;     // running max (of scaled scores, log2 domain) and this lane's partial sum
 
-  uint4 rk[K_CHUNKS], rv[8];
-  const bool v_thread = tid < 8 * CH;
-  const int v_kb = tid / CH, v_dc = tid % CH;   // 8x8 block: keys v_kb*8.., dims v_dc*8..
+  uint4 rk[K_CHUNKS], rv[4];
+  const bool v_thread = tid < 16 * CH;          // 4 keys x 8 dims per thread
+  // The 4-key blocks are numbered so that the two blocks a 32-lane write phase touches differ in the
+  // half of the 16-byte chunk they fill (2-deep bank conflicts at most).
+  const int v_a = tid / CH, v_dc = tid % CH;
+  const int v_k4 = (v_a & ~3) | ((v_a & 1) << 1) | ((v_a >> 1) & 1);
   auto load_global = [&](int k0) {
 #pragma unroll
     for (int c = 0; c < K_CHUNKS; ++c) {
@@ -353,8 +146,8 @@ __global__ __launch_bounds__(256) void attention_mfma_short_kernel(const uint16_
     }
     if (v_thread) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int key = k0 + v_kb * 8 + i;
+      for (int i = 0; i < 4; ++i) {
+        const int key = k0 + v_k4 * 4 + i;
         rv[i] = key < T ? *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(key) * 3 * D + 2 * D + v_dc * 8) : make_uint4(0, 0, 0, 0);
       }
     }
@@ -367,23 +160,20 @@ __global__ __launch_bounds__(256) void attention_mfma_short_kernel(const uint16_
       if (id < 64 * CH) *reinterpret_cast<uint4*>(Ks + (buf * 64 + key) * KST + dc * 8) = rk[c];
     }
     if (v_thread) {
-      // rv[i] = 8 dims of key i  ->  8 rows (dims) of 8 keys
-      const uint32_t w[8][4] = {{rv[0].x, rv[0].y, rv[0].z, rv[0].w}, {rv[1].x, rv[1].y, rv[1].z, rv[1].w},
-                                {rv[2].x, rv[2].y, rv[2].z, rv[2].w}, {rv[3].x, rv[3].y, rv[3].z, rv[3].w},
-                                {rv[4].x, rv[4].y, rv[4].z, rv[4].w}, {rv[5].x, rv[5].y, rv[5].z, rv[5].w},
-                                {rv[6].x, rv[6].y, rv[6].z, rv[6].w}, {rv[7].x, rv[7].y, rv[7].z, rv[7].w}};
+      // rv[i] = 8 dims of key i  ->  8 rows (dims) of 4 keys
+      const uint32_t w[4][4] = {{rv[0].x, rv[0].y, rv[0].z, rv[0].w}, {rv[1].x, rv[1].y, rv[1].z, rv[1].w},
+                                {rv[2].x, rv[2].y, rv[2].z, rv[2].w}, {rv[3].x, rv[3].y, rv[3].z, rv[3].w}};
+      const int c_ = 2 * (v_k4 >> 2) + (v_k4 & 1), h_ = (v_k4 >> 1) & 1;
 #pragma unroll
       for (int dd = 0; dd < 8; ++dd) {
-        uint32_t r[4];
+        const int d_ = v_dc * 8 + dd;
+        uint32_t r[2];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
+        for (int kk = 0; kk < 2; ++kk) {
           const uint32_t a = w[2 * kk][dd >> 1], b = w[2 * kk + 1][dd >> 1];
           r[kk] = (dd & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
         }
-        int lo_, hi_;
-        vt_write_off<64>(v_dc * 8 + dd, v_kb, &lo_, &hi_);
-        *reinterpret_cast<uint2*>(Vt + buf * VTILE + lo_) = make_uint2(r[0], r[1]);
-        *reinterpret_cast<uint2*>(Vt + buf * VTILE + hi_) = make_uint2(r[2], r[3]);
+        *reinterpret_cast<uint2*>(Vt + buf * VTILE + d_ * 64 + ((c_ ^ vt_swz<64>(d_)) << 3) + 4 * h_) = make_uint2(r[0], r[1]);
       }
     }
   };
@@ -446,8 +236,8 @@ __global__ __launch_bounds__(256) void attention_mfma_short_kernel(const uint16_
     for (int t = 0; t < 4; ++t) {
       const int st = t >> 1, j0 = (t & 1) * 8;      // accumulator entries j0 .. j0+7 of sub-tile st
       Frag pf;
-      pf.u = make_uint4(pack_bf16(s[st][j0], s[st][j0 + 1]), pack_bf16(s[st][j0 + 2], s[st][j0 + 3]),
-                        pack_bf16(s[st][j0 + 4], s[st][j0 + 5]), pack_bf16(s[st][j0 + 6], s[st][j0 + 7]));
+      pf.u = make_uint4(cvt_pk_bf16(s[st][j0], s[st][j0 + 1]), cvt_pk_bf16(s[st][j0 + 2], s[st][j0 + 3]),
+                        cvt_pk_bf16(s[st][j0 + 4], s[st][j0 + 5]), cvt_pk_bf16(s[st][j0 + 6], s[st][j0 + 7]));
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         Frag vf;
@@ -471,8 +261,8 @@ __global__ __launch_bounds__(256) void attention_mfma_short_kernel(const uint16_
         const int d = dt * 32 + 8 * jj + 4 * lhi;
         if (d < HD) {
           uint2 r;
-          r.x = pack_bf16(o[dt][4 * jj] * inv, o[dt][4 * jj + 1] * inv);
-          r.y = pack_bf16(o[dt][4 * jj + 2] * inv, o[dt][4 * jj + 3] * inv);
+          r.x = cvt_pk_bf16(o[dt][4 * jj] * inv, o[dt][4 * jj + 1] * inv);
+          r.y = cvt_pk_bf16(o[dt][4 * jj + 2] * inv, o[dt][4 * jj + 3] * inv);
           *reinterpret_cast<uint2*>(op + d) = r;
         }
       }
@@ -658,12 +448,10 @@ Error launch_hd(const void* qkv, void* out, int64_t ldo, int rows, int T, int H,
     SPECA_HIP(hipGetLastError());
     return ok();
   }
-  const bool pipelined = T > 512;      // measured: the pipelined kernel wins from ~8 key tiles on
-  auto kern = pipelined ? attention_mfma_kernel<HD> : attention_mfma_short_kernel<HD>;
+  auto kern = attention_mfma_kernel<HD>;
   static bool attr_set = false;
   if (smem > 64 * 1024 && !attr_set) {
     SPECA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attention_mfma_kernel<HD>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem)));
-    SPECA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attention_mfma_short_kernel<HD>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem)));
     attr_set = true;
   }
   dim3 grid((T + 127) / 128, H, rows);
