@@ -320,14 +320,20 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const uint16_t
 // the same chunk index of 16 consecutive rows then touch all 64 banks exactly once.
 // Loader: one load instruction fills 8 rows (64 chunks, 1 KiB, contiguous in LDS); lane l supplies
 // the chunk stored at position l % 8 of row l / 8, i.e. source chunk (l % 8) ^ swz(row), and the
-// hardware places lane l's 16 bytes at the wave-uniform LDS address + 16 l.  Wave w owns the row
-// groups w, w + NW, ...; NW is even, so swz depends only on the lane and the wave's parity.
-// Rows beyond M / N are clamped to the last row (never stored), K-steps beyond the last re-read
-// the last one into a stage nobody reads again, so every wave issues the same number of loads per
-// step and "all but the newest (NS-2) steps have landed" is one immediate vmcnt value.
-// Ring discipline per K-step: wait own loads of this step; barrier (everyone's loads of this step
-// are in LDS and everyone is done reading the previous step's stage); issue the loads of step
-// kt + NS - 1 into the stage just freed; compute.
+// hardware places lane l's 16 bytes at the wave-uniform LDS address + 16 l.  A loader wave owns the
+// row groups wl, wl + NL, ... (NL loader waves, NL even, so swz depends only on the lane and the
+// parity of wl).  Rows beyond M / N are clamped to the last row (never stored).
+//
+// Completion of these loads is only ever awaited with vmcnt(0).  A partial wait ("all but the newest
+// six have landed") assumes they complete in issue order; they do not reliably: a 3-stage ring built
+// on vmcnt(6) passed every isolated test and then delivered stale operand rows (32-row groups, a few
+// launches per step) once four row groups ran side by side.  Two loads-in-flight stages with
+// vmcnt(0)-only waits are obtained by splitting the waves into two loader groups instead: group g
+// loads the K-steps of parity g, so at its wait a group has exactly one step outstanding (the one
+// everybody needs next) while the other group's step stays in flight.
+// Ring discipline per K-step kt (NS = 2: every wave loads every step; NS = 3: two groups):
+//   the step's loader waves wait vmcnt(0); barrier (the step is in LDS, everyone is done reading the
+//   previous step's stage); the same waves issue step kt + NS - 1 into the stage just freed; compute.
 #define SPECA_GLL(src, dst)                                                                                       \
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),                         \
                                    (__attribute__((address_space(3))) void*)(dst), 16, 0, 0)
@@ -345,9 +351,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t
   constexpr int NW = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int AG = BM / 8 / NW, WG = BN / 8 / NW;         // 8-row groups (one load instruction each) per wave
-  static_assert(BM / 8 % NW == 0 && BN / 8 % NW == 0 && NW % 2 == 0, "row groups must divide among an even number of waves");
   static_assert(NS == 2 || NS == 3, "ring depth");
+  constexpr int NL = NS == 3 ? NW / 2 : NW;                  // loader waves per K-step
+  constexpr int AG = BM / 8 / NL, WG = BN / 8 / NL;          // 8-row groups (one load instruction each) per loader wave
+  static_assert(BM / 8 % NL == 0 && BN / 8 % NL == 0 && NL % 2 == 0, "row groups must divide among an even number of loader waves");
   constexpr int STAGE = (BM + BN) * BK;                      // elements per stage
   constexpr int EH = dlds_epilogue_rows(BM, BN, NS);
   extern __shared__ __align__(16) uint16_t smem[];
@@ -369,19 +376,20 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;
 
   const int nk = K / BK;
+  const int grp = wave / NL, wl = wave % NL;                 // loader group (NS = 3) and index inside it
   const int lrow = lane >> 3;
-  const int lchunk = (lane & 7) ^ lrow ^ (wave & 1);
+  const int lchunk = (lane & 7) ^ lrow ^ (wl & 1);
   const uint16_t* pa[AG];
   const uint16_t* pw[WG];
 #pragma unroll
   for (int g = 0; g < AG; ++g) {
-    const int row = (wave + g * NW) * 8 + lrow;
+    const int row = (wl + g * NL) * 8 + lrow;
     const int m = m0 + row < M ? m0 + row : M - 1;
     pa[g] = A + static_cast<int64_t>(m) * lda + lchunk * 8;
   }
 #pragma unroll
   for (int g = 0; g < WG; ++g) {
-    const int row = (wave + g * NW) * 8 + lrow;
+    const int row = (wl + g * NL) * 8 + lrow;
     const int n = n0 + row < N ? n0 + row : N - 1;
     pw[g] = W + static_cast<int64_t>(n) * ldw + lchunk * 8;
   }
@@ -393,9 +401,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t
 
 #define SPECA_LOADS(st, kt_)                                                                                      \
   {                                                                                                               \
-    const int k0_ = ((kt_) < nk ? (kt_) : nk - 1) * BK;                                                           \
-    _Pragma("unroll") for (int g = 0; g < AG; ++g) SPECA_GLL(pa[g] + k0_, smem + (st) * STAGE + (wave + g * NW) * 512);           \
-    _Pragma("unroll") for (int g = 0; g < WG; ++g) SPECA_GLL(pw[g] + k0_, smem + (st) * STAGE + BM * BK + (wave + g * NW) * 512); \
+    const int k0_ = (kt_) * BK;                                                                                   \
+    _Pragma("unroll") for (int g = 0; g < AG; ++g) SPECA_GLL(pa[g] + k0_, smem + (st) * STAGE + (wl + g * NL) * 512);           \
+    _Pragma("unroll") for (int g = 0; g < WG; ++g) SPECA_GLL(pw[g] + k0_, smem + (st) * STAGE + BM * BK + (wl + g * NL) * 512); \
   }
 #define SPECA_LDFRAG(fa_, fw_, ks_)                                                                               \
   {                                                                                                               \
@@ -422,39 +430,23 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t
     SPECA_MFMAS(fa0, fw0);                                                                                        \
     SPECA_MFMAS(fa1, fw1);                                                                                        \
   }
-  constexpr int LPW = AG + WG;                               // load instructions per wave per step
-  constexpr int VM = (NS - 2) * LPW;                         // loads that may still be in flight at the wait
-  static_assert(VM < 64, "vmcnt range");
-  constexpr int WAIT_VM = (VM & 0xF) | ((VM >> 4) << 14) | 0x0F70;   // s_waitcnt vmcnt(VM), other counters untouched
-  constexpr int WAIT_VM0 = 0x0F70;
-#define SPECA_STEP(st_cur, st_new, kt_)                                                                           \
-  {                                                                                                               \
-    __builtin_amdgcn_s_waitcnt(WAIT_VM);                                                                          \
-    __builtin_amdgcn_s_barrier();                                                                                 \
-    SPECA_LOADS(st_new, (kt_) + NS - 1);                                                                          \
-    SPECA_COMPUTE(st_cur);                                                                                        \
-  }
+  constexpr int WAIT_VM0 = 0x0F70;                           // s_waitcnt vmcnt(0), other counters untouched
+  // prologue: steps 0 .. NS-2, each by its loader waves
 #pragma unroll
-  for (int s = 0; s < NS - 1; ++s) SPECA_LOADS(s, s);
-  if (NS == 3) {
-    int kt = 0;
-    for (; kt + 3 <= nk; kt += 3) {
-      SPECA_STEP(0, 2, kt);
-      SPECA_STEP(1, 0, kt + 1);
-      SPECA_STEP(2, 1, kt + 2);
-    }
-    if (kt < nk) {
-      SPECA_STEP(0, 2, kt);
-      if (kt + 1 < nk) SPECA_STEP(1, 0, kt + 1);
-    }
-  } else {
-    for (int kt = 0; kt < nk; kt += 2) {
-      SPECA_STEP(0, 1, kt);
-      if (kt + 1 < nk) SPECA_STEP(1, 0, kt + 1);
-    }
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < nk && (NS == 2 || grp == (s & 1))) SPECA_LOADS(s, s);
+  int cur = 0;                                               // stage of step kt
+  for (int kt = 0; kt < nk; ++kt) {
+    const bool mine = NS == 2 || grp == (kt & 1);            // wave-uniform
+    if (mine) __builtin_amdgcn_s_waitcnt(WAIT_VM0);          // my only outstanding loads are those of step kt
+    __builtin_amdgcn_s_barrier();
+    const int nxt = kt + NS - 1;
+    const int st_new = cur == 0 ? NS - 1 : cur - 1;          // the stage read during step kt - 1
+    if (mine && nxt < nk) SPECA_LOADS(st_new, nxt);
+    SPECA_COMPUTE(cur);
+    cur = cur + 1 == NS ? 0 : cur + 1;
   }
-  __builtin_amdgcn_s_waitcnt(WAIT_VM0);                      // the clamped extra loads must have landed before LDS is reused
-#undef SPECA_STEP
+  __builtin_amdgcn_s_waitcnt(WAIT_VM0);                      // nothing is outstanding here; kept as a guard before LDS is reused
 #undef SPECA_COMPUTE
 #undef SPECA_MFMAS
 #undef SPECA_LDFRAG
@@ -556,7 +548,7 @@ Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, i
   // and on FLUX-sized ones (M 4608, N 3072..12288, K 3072..12288):
   //   256x256, 8 waves (wave tile 64x128): fewest L2 -> LDS bytes per FLOP; wins once K is long and the
   //     problem still gives most CUs a tile (one block per CU);
-  //   256x128, 8 waves, 3-stage ring: medium problems;
+  //   256x128, 8 waves, 2- or 3-stage ring: medium problems;
   //   128x128, 4 waves, register-staged loop, two blocks per CU: wide N with short K (inside a step the
   //     direct-to-LDS 128x128 tile measured 75 us against 65 us on the 4096 x 4608 x 1152 MLP GEMM,
   //     although it wins in isolation: with one K-step of prefetch it is more exposed to HBM latency
@@ -569,7 +561,12 @@ Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, i
   static const bool staged_only = [] { const char* e = getenv("SPECA_GEMM_LOOP"); return e && e[0] == 's'; }();
   if (K % BK == 0 && M >= 256 && !staged_only) {
     if (K >= 2048 && t256s >= 200) return launch_dlds<256, 256, 4, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
-    if (t256 >= 128 && t128 <= 1024) return launch_dlds<256, 128, 4, 2, 3>(A, lda, W, ldw, M, N, K, epi, st);
+    if (t256 >= 128 && t128 <= 1024) {
+      // at most one tile per CU and a short K loop: the 2-stage ring (96 KiB of LDS leave room for a block of
+      // another launch on the same CU when row groups run side by side); otherwise two loader groups, 3 stages
+      if (t256 < 256 && K < 2048) return launch_dlds<256, 128, 4, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
+      return launch_dlds<256, 128, 4, 2, 3>(A, lda, W, ldw, M, N, K, epi, st);
+    }
   }
   if (t256 >= 128 && (t128 <= 1024 || (K >= 2048 && t128 >= 2048)) && M >= 256) return launch_tile<256, 128, 4, 2>(A, lda, W, ldw, M, N, K, epi, st);
   if (t128 >= 200) return launch_tile<128, 128, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);

@@ -245,3 +245,37 @@ def test_config2_full_size_sampled():
     assert acc.tolist() == [True] * 4 + [False] * 4
     assert np.min(np.abs(exp - 0.05) / 0.05) > 0.15
     ctx.close()
+
+
+def test_row_list_limits():
+    """Empty, maximum-size and over-size row lists (one launch carries at most 64 rows)."""
+    sp = _sp()
+    from paper_2509_11628_amd import binding as bd
+    slots, B, T, D = 1, 70, 4, 8
+    ctx = sp.Context(sp.cache_only_desc(slots, T, D, bd.F32))
+    ctx.init_cache(sp.make_cfg(order=1, interval=4), B)
+    rng = np.random.default_rng(0)
+    f0 = rng.standard_normal((slots, B, T, D)).astype(np.float32)
+    f1 = rng.standard_normal((slots, B, T, D)).astype(np.float32)
+    oc = _oracle_caches(B, slots, 1, "taylor", "f32")
+    for s_, f in ((0, f0), (3, f1)):
+        for lo, hi in ((0, 64), (64, 70)):                # 64 rows: the largest single launch, then the ragged rest
+            rows = list(range(lo, hi))
+            ctx.refresh(s_, rows, _dev(np.ascontiguousarray(f[:, lo:hi]), "f32"))
+        for r in range(B):
+            oc[r].refresh(s_, [f[j, r] for j in range(slots)])
+    out = torch.empty((slots, 64, T, D), dtype=torch.float32, device="cuda")
+    ctx.forecast(5, list(range(64)), out)
+    exp = np.stack([np.stack([oc[r].forecast(5, j) for r in range(64)]) for j in range(slots)])
+    assert max_abs_rel(_host(out), exp) <= 1e-5
+    big = torch.empty((slots, 65, T, D), dtype=torch.float32, device="cuda")
+    with pytest.raises(sp.SpecaError) as e:
+        ctx.forecast(5, list(range(65)), big)
+    assert e.value.code in (bd.EUNSUPPORTED, bd.EINVAL)
+    with pytest.raises(sp.SpecaError) as e:
+        ctx.forecast(5, [], out)
+    assert e.value.code == bd.EINVAL
+    with pytest.raises(sp.SpecaError) as e:
+        ctx.refresh(6, [], out)
+    assert e.value.code == bd.EINVAL
+    ctx.close()

@@ -276,3 +276,52 @@ def test_lanes_do_not_change_results(tiny):
     with pytest.raises(sp.SpecaError) as e:
         ctx.set_lanes(9)
     assert e.value.code == bd.EINVAL
+
+
+def test_config3_full_size_sampled():
+    """Configuration 3 at full size, in the launch shape the benchmark times (16 rows = 8 samples x
+    guidance pair, bf16, 4 lanes): the reference step of one guidance pair (rows 0 and 8) against the
+    oracle's forward of those two rows (about 10 s of CPU), model output and sampled cached features;
+    then properties that hold at any size: thresholds of zero reproduce plain sampling bit for bit and
+    the lane count does not change a bit."""
+    import paper_2509_11628_amd as sp
+    from paper_2509_11628_amd import binding as bd
+    s = si.dit_xl2("bf16")
+    w = si.make_dit_weights(s, 0)
+    ctx = sp.Context(sp.dit_desc(s), sp.to_device(w, bd.BF16))
+    B = 8
+    ctx.set_lanes(4)
+    ctx.init_cache(sp.make_cfg(order=2, interval=5), 2 * B)
+    lat = si.make_latents(B, s.in_channels, s.latent_hw, 0)
+    lab = si.make_labels(B, s.num_classes, 0)
+    labels_rows = list(lab) + [s.num_classes] * B                    # conditional rows, then null-label rows
+    xd = torch.from_numpy(np.concatenate([lat, lat])).cuda()          # one latent row per cache row
+    out = torch.zeros_like(xd)
+    ts, ab = si.ddim_tables(50)
+    ctx.full_step(xd, 0, list(range(2 * B)), out, timestep=float(ts[0]), labels=labels_rows)
+    om = odit.DiTOracle(s, w)
+    exp, feats = om.forward(np.stack([lat[0], lat[0]]), float(ts[0]), [int(lab[0]), s.num_classes])
+    got = out.cpu().numpy()
+    assert max_abs_rel(got[[0, B]], exp) <= 2e-2
+    f = torch.empty((s.n_slots, 2, s.tokens, s.hidden), dtype=torch.bfloat16, device="cuda")
+    ctx.forecast(1, [0, B], f)                                        # one reference: the forecast is the cached feature
+    gf = f.float().cpu().numpy()
+    rng = np.random.default_rng(0)
+    for j in (0, 1, 27, 54, 55):
+        idx = (rng.integers(0, 2, 2000), rng.integers(0, s.tokens, 2000), rng.integers(0, s.hidden, 2000))
+        a, b = gf[j][idx], feats[j][idx]
+        assert np.max(np.abs(a - b)) <= 2e-2 * np.max(np.abs(feats[j])), j
+    # properties at full size: tau = 0 is plain sampling; lanes do not change bits (8 steps keep it short)
+    S = 8
+    ts, ab = si.ddim_tables(S)
+    res = []
+    for lanes, tau in ((4, np.zeros(S, np.float32)), (1, np.zeros(S, np.float32)), (4, bd.tau_geometric(0.5, 0.5, S)), (2, bd.tau_geometric(0.5, 0.5, S))):
+        ctx.set_lanes(lanes)
+        ctx.init_cache(sp.make_cfg(order=2, interval=4), 2 * B)
+        x = torch.from_numpy(lat).cuda()
+        tr = ctx.sample(x, ts, ab, tau, cfg_scale=1.5, labels=lab)
+        res.append((x.cpu().numpy(), tr))
+    assert np.all(res[0][1]["kind"] == 0) and np.array_equal(res[0][0], res[1][0])
+    assert np.array_equal(res[2][0], res[3][0]) and np.array_equal(res[2][1]["kind"], res[3][1]["kind"])
+    assert np.all(np.isfinite(res[2][0]))
+    ctx.close()
