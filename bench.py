@@ -209,16 +209,17 @@ def bench_mmdit(args, which):
         dt = time.perf_counter() - t0
         prof = ctx.profile_end() if profile else None
         assert bool(torch.isfinite(x).all()), "non-finite latents"
-        return dt, tr, prof
+        return dt, tr, prof, x
 
     K = args.steps
     tau = bd.tau_geometric(args.tau0, args.tau_end / args.tau0, K)
     if args.warmup > 0:
         run(args.warmup, bd.tau_geometric(args.tau0, args.tau_end / args.tau0, args.warmup))
-    dt, tr, _ = run(K, tau)
-    _, _, prof = run(K, tau, profile=True)
-    dt_plain, tr_plain, _ = run(K, np.zeros(K, np.float32))
-    dt_acc, tr_acc, _ = run(K, np.full(K, np.inf, np.float32))
+    dt, tr, _, x_timed = run(K, tau)
+    _, _, prof, x_prof = run(K, tau, profile=True)
+    assert torch.equal(x_timed, x_prof), "the same trajectory gave different bits on a second run"
+    dt_plain, tr_plain, _, _ = run(K, np.zeros(K, np.float32))
+    dt_acc, tr_acc, _, _ = run(K, np.full(K, np.inf, np.float32))
     assert tr_plain["n_spec"] == 0 and tr_acc["kind"][0].tolist() == [0 if i % args.interval == 0 else 1 for i in range(K)]
     dom = max(("gemm", "attention", "forecast", "verify", "other"), key=lambda k: prof[k]["ms"])
     p = prof[dom]
@@ -307,16 +308,18 @@ def main():
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         prof = ctx.profile_end() if profile else None
-        return dt, tr, prof
+        return dt, tr, prof, x
 
     if args.warmup > 0:
         run(args.warmup)
     K = args.steps
-    dt, tr, _ = run(K)
-    _, _, prof = run(K, profile=True)
+    dt, tr, _, x_timed = run(K)
+    _, _, prof, x_prof = run(K, profile=True)
+    # the profiled pass runs the row groups serially, the timed one side by side: same bits required
+    assert torch.equal(x_timed, x_prof), "lanes changed the result"
     # the same trajectory without speculation (tau = 0: plain sampling) and with every attempt accepted
-    dt_plain, _, _ = run(K, tau=np.zeros(K, np.float32))
-    dt_acc, tr_acc, _ = run(K, tau=np.full(K, np.inf, np.float32))
+    dt_plain, _, _, _ = run(K, tau=np.zeros(K, np.float32))
+    dt_acc, tr_acc, _, _ = run(K, tau=np.full(K, np.inf, np.float32))
 
     dom = max(("gemm", "attention", "forecast", "verify", "other"), key=lambda k: prof[k]["ms"])
     p = prof[dom]
