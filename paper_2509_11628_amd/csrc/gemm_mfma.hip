@@ -435,17 +435,33 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s)
     if (s < nk && (NS == 2 || grp == (s & 1))) SPECA_LOADS(s, s);
-  int cur = 0;                                               // stage of step kt
-  for (int kt = 0; kt < nk; ++kt) {
-    const bool mine = NS == 2 || grp == (kt & 1);            // wave-uniform
-    if (mine) __builtin_amdgcn_s_waitcnt(WAIT_VM0);          // my only outstanding loads are those of step kt
-    __builtin_amdgcn_s_barrier();
-    const int nxt = kt + NS - 1;
-    const int st_new = cur == 0 ? NS - 1 : cur - 1;          // the stage read during step kt - 1
-    if (mine && nxt < nk) SPECA_LOADS(st_new, nxt);
-    SPECA_COMPUTE(cur);
-    cur = cur + 1 == NS ? 0 : cur + 1;
+  // One K-step with compile-time stage numbers and loader parity (the ring has period NS, the loader
+  // groups period 2: the loop body is unrolled over their common period so every LDS address is an
+  // immediate offset).
+#define SPECA_STEP(kt_, cur_, new_, par_)                                                                         \
+  {                                                                                                               \
+    const bool mine_ = NS == 2 || grp == (par_);             /* wave-uniform */                                    \
+    if (mine_) __builtin_amdgcn_s_waitcnt(WAIT_VM0);         /* my only outstanding loads are those of this step */ \
+    __builtin_amdgcn_s_barrier();                                                                                 \
+    if (mine_ && (kt_) + NS - 1 < nk) SPECA_LOADS(new_, (kt_) + NS - 1);                                          \
+    SPECA_COMPUTE(cur_);                                                                                          \
   }
+  if (NS == 2) {
+    for (int kt = 0; kt < nk; kt += 2) {
+      SPECA_STEP(kt, 0, 1, 0);
+      if (kt + 1 < nk) SPECA_STEP(kt + 1, 1, 0, 0);
+    }
+  } else {
+    for (int kt = 0; kt < nk; kt += 6) {
+      SPECA_STEP(kt, 0, 2, 0);
+      if (kt + 1 < nk) SPECA_STEP(kt + 1, 1, 0, 1);
+      if (kt + 2 < nk) SPECA_STEP(kt + 2, 2, 1, 0);
+      if (kt + 3 < nk) SPECA_STEP(kt + 3, 0, 2, 1);
+      if (kt + 4 < nk) SPECA_STEP(kt + 4, 1, 0, 0);
+      if (kt + 5 < nk) SPECA_STEP(kt + 5, 2, 1, 1);
+    }
+  }
+#undef SPECA_STEP
   __builtin_amdgcn_s_waitcnt(WAIT_VM0);                      // nothing is outstanding here; kept as a guard before LDS is reused
 #undef SPECA_COMPUTE
 #undef SPECA_MFMAS
