@@ -576,7 +576,7 @@ Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, i
   // SPECA_GEMM_LOOP=staged keeps every shape on the register-staged loop (A/B timing of the two loops)
   static const bool staged_only = [] { const char* e = getenv("SPECA_GEMM_LOOP"); return e && e[0] == 's'; }();
   if (K % BK == 0 && M >= 256 && !staged_only) {
-    if (K >= 2048 && t256s >= 200) return launch_dlds<256, 256, 4, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
+    if (K >= 2048 && t256s >= 160) return launch_dlds<256, 256, 4, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
     if (t256 >= 128 && t128 <= 1024) {
       // at most one tile per CU and a short K loop: the 2-stage ring (96 KiB of LDS leave room for a block of
       // another launch on the same CU when row groups run side by side); otherwise two loader groups, 3 stages
