@@ -128,7 +128,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const uint16_t* 
   for (int i = 0; i < DT; ++i)
 #pragma unroll
     for (int q = 0; q < 16; ++q) o[i][q] = 0.0f;
-  float mrun = -INFINITY, lrun = 0.0f;     // running max (of scaled scores, log2 domain) and this lane's partial sum
+  float mrun = -INFINITY, lrun = 0.0f;     // running max of the raw scores and this lane's partial sum
 
   uint4 rk[K_CHUNKS], rv[4];
   const bool v_thread = tid < 16 * CH;          // 4 keys x 8 dims per thread
@@ -200,36 +200,45 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const uint16_t* 
         s[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, s[st], 0, 0, 0);
       }
     }
-    // scale to the log2 domain, mask the ragged tail, row max over the lane pair
-    float tmax = -INFINITY;
+    // mask the ragged tail (last tile only), row max of the raw scores over the lane pair
     const int kbase = kt * 64;
+    if (kbase + 64 > T) {
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          const int key = kbase + st * 32 + 8 * (q >> 2) + 4 * lhi + (q & 3);
+          if (key >= T) s[st][q] = -INFINITY;
+        }
+    }
+    float tmax = -INFINITY;
 #pragma unroll
     for (int st = 0; st < 2; ++st)
 #pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const int key = kbase + st * 32 + 8 * (q >> 2) + 4 * lhi + (q & 3);
-        const float v = key < T ? s[st][q] * scale_log2e : -INFINITY;
-        s[st][q] = v;
-        tmax = fmaxf(tmax, v);
-      }
+      for (int q = 0; q < 16; ++q) tmax = fmaxf(tmax, s[st][q]);
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    // mrun is the running maximum of the RAW scores; the scale (> 0) and log2(e) enter in one fma per score
     const float mnew = fmaxf(mrun, tmax);
-    const float corr = fast_exp2(mrun - mnew);
-    mrun = mnew;
+    const float moff = mnew * scale_log2e;
     float psum = 0.0f;
 #pragma unroll
     for (int st = 0; st < 2; ++st)
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
-        const float p = fast_exp2(s[st][q] - mnew);
+        const float p = fast_exp2(fmaf(s[st][q], scale_log2e, -moff));
         s[st][q] = p;
         psum += p;
       }
-    lrun = lrun * corr + psum;
+    if (__any(mnew != mrun)) {       // the running maximum moved somewhere in the wave: rescale (rare after the first tiles)
+      const float corr = fast_exp2(mrun * scale_log2e - moff);
+      lrun *= corr;
 #pragma unroll
-    for (int i = 0; i < DT; ++i)
+      for (int i = 0; i < DT; ++i)
 #pragma unroll
-      for (int q = 0; q < 16; ++q) o[i][q] *= corr;
+        for (int q = 0; q < 16; ++q) o[i][q] *= corr;
+      mrun = mnew;
+    }
+    lrun += psum;
 
     // O^T += V^T P^T, four reduction steps of 16 keys
 #pragma unroll
@@ -372,23 +381,26 @@ __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_
         kf.u = *reinterpret_cast<const uint4*>(kp + ks * 16);
         s[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, s[st], 0, 0, 0);
       }
+      if (st * 32 + 32 > T) {                  // ragged last sub-tile
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int key = st * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
-        const float v = key < T ? s[st][e] * scale_log2e : -INFINITY;
-        s[st][e] = v;
-        tmax = fmaxf(tmax, v);
+        for (int e = 0; e < 16; ++e) {
+          const int key = st * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
+          if (key >= T) s[st][e] = -INFINITY;
+        }
       }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, s[st][e]);
     }
   }
-  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));     // maximum of the raw scores; scale and log2(e) enter in the fma below
+  const float moff = tmax * scale_log2e;
   float psum = 0.0f;
 #pragma unroll
   for (int st = 0; st < NST; ++st)
     if (st < nst) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const float p = fast_exp2(s[st][e] - tmax);
+        const float p = fast_exp2(fmaf(s[st][e], scale_log2e, -moff));
         s[st][e] = p;
         psum += p;
       }
