@@ -20,8 +20,8 @@
 //   gemm_dlds_kernel  operands go global -> LDS directly (global_load_lds_dwordx4: a wave writes 64
 //                     consecutive 16-byte chunks at a wave-uniform LDS address), no register staging,
 //                     no LDS stores; unpadded 128-byte LDS rows with an XOR swizzle of the chunk
-//                     position; ring of NS stages with one raw barrier per K-step and an exact
-//                     vmcnt wait.  Needs K % 64 == 0.  Tiles 256x128 and 256x256 (half the L2 -> LDS
+//                     position; ring of NS stages with one raw barrier per K-step, loads awaited with
+//                     vmcnt(0) by the waves that issued them.  Needs K % 64 == 0.  Tiles 256x128 and 256x256 (half the L2 -> LDS
 //                     bytes per FLOP of 128x128).
 //   gemm_mfma_kernel  the register-staged loop described above: K tails, small problems.
 #include <cstdlib>
