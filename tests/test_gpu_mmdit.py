@@ -120,3 +120,33 @@ def test_mmdit_error_paths(tiny):
     with pytest.raises(sp.SpecaError) as e:
         make_gpu(s, bad)
     assert e.value.code == bd.EINVAL and "single0.lin2_w" in e.value.msg
+
+
+def test_flux_width_slice_matches_oracle():
+    """One dual-stream and one single-stream block at the full FLUX width (D 3072, 24 heads of 128,
+    MLP 12288) on 128 + 1280 tokens: the 256x256 and 256x128 GEMM tiles, the K lengths of
+    configuration 4 (3072, 12288, 15360) and the tiled attention over 22 key tiles, against the
+    oracle's forward (about a minute of CPU).  The benchmark's model differs in depth and token count."""
+    import dataclasses
+    import paper_2509_11628_amd as sp
+    s = dataclasses.replace(si.mmdit_flux("bf16"), depth_dual=1, depth_single=1, latent_h=64, latent_w=80, txt_tokens=128)
+    w = si.make_mmdit_weights(s, 0)
+    om = ommdit.MMDiTOracle(s, w)
+    ctx = make_gpu(s, w)
+    x = si.make_video_latents(1, s, 3); txt, vec = si.make_text(1, s, 3)
+    ctx.init_cache(sp.make_cfg(order=2, interval=5), 1)
+    xd = torch.from_numpy(x).cuda()
+    td, vd = torch.from_numpy(txt).cuda().bfloat16(), torch.from_numpy(vec).cuda().bfloat16()
+    out = torch.zeros_like(xd)
+    ctx.full_step(xd, 0, [0], out, timestep=0.7, txt=td, pooled=vd)
+    exp, feats = om.forward(x, 0.7, (txt, vec))
+    assert max_abs_rel(out.cpu().numpy(), exp) <= 2e-2
+    f = torch.empty((s.n_slots, 1, s.tokens, s.hidden), dtype=torch.bfloat16, device="cuda")
+    ctx.forecast(1, [0], f)
+    got = f.float().cpu().numpy()
+    rng = np.random.default_rng(0)
+    for j in range(s.n_slots):
+        idx = (np.zeros(4000, np.int64), rng.integers(0, s.tokens, 4000), rng.integers(0, s.hidden, 4000))
+        idx[1][:2] = [0, s.tokens - 1]; idx[2][:2] = [0, s.hidden - 1]
+        assert np.max(np.abs(got[j][idx] - feats[j][idx])) <= 2e-2 * np.max(np.abs(feats[j])), j
+    ctx.close()
