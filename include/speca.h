@@ -21,7 +21,9 @@
  *     tensors) unless stated otherwise; HOST pointers are ordinary process memory.
  *   - Every function returns a speca_status; it never throws or aborts.  The message of
  *     the last failure on a context is available from speca_last_error().
- *   - All device work of a context is enqueued on the HIP stream given at creation.
+ *   - All device work of a context is enqueued on the HIP stream given at creation, or on
+ *     library-owned streams forked from and joined back to it inside a call (speca_set_lanes),
+ *     so a caller sees ordinary stream order on that stream.
  *     Calls that return host results (speca_verify, speca_spec_step, speca_sample)
  *     synchronise that stream before returning; the others are asynchronous.
  *   - A context is not thread-safe; contexts are independent of each other.
