@@ -331,6 +331,7 @@ def main():
         ach = p["bytes"] / (p["ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "traffic": None}
     roof["traffic"] = MEASURED_TRAFFIC.get(("dit_xl2", dom))
+    roof["measured_on"] = "same trajectory, row groups run serially on one stream (per-kernel event times need no overlap); value is timed with lanes"
     roof.update({"kernel": dom, "launches": p["launches"], "avg_launch_us": 1e3 * p["ms"] / max(p["launches"], 1),
                  "flops_per_launch": p["flops"] / max(p["launches"], 1), "bytes_per_launch": p["bytes"] / max(p["launches"], 1)})
 
