@@ -324,4 +324,20 @@ def test_config3_full_size_sampled():
     assert np.all(res[0][1]["kind"] == 0) and np.array_equal(res[0][0], res[1][0])
     assert np.array_equal(res[2][0], res[3][0]) and np.array_equal(res[2][1]["kind"], res[3][1]["kind"])
     assert np.all(np.isfinite(res[2][0]))
+    # a short trajectory in the benchmark's launch shape (8 samples, guidance, 4 lanes) with an accepted, a
+    # rejected and another accepted attempt; sample 0 against the oracle run on that sample alone
+    # (samples are independent: own cache, own schedule)
+    S = 4
+    ts, ab = si.ddim_tables(S)
+    tau = np.array([0.0, np.inf, 1e-3, np.inf], np.float32)
+    ctx.set_lanes(4)
+    ctx.init_cache(sp.make_cfg(order=2, interval=5), 2 * B)
+    x = torch.from_numpy(lat).cuda()
+    gtr = ctx.sample(x, ts, ab, tau, cfg_scale=1.5, labels=lab)
+    sol = osamp.Solver("ddim", ts, ab, 1.5)
+    exp1, tr = osamp.sample(om, osamp.SpecaConfig(order=2, interval=5, cache_store="bf16"), sol, tau, lat[:1], lab[:1])
+    assert tr.kind[0].tolist() == [0, 1, 2, 1] and gtr["kind"][0].tolist() == [0, 1, 2, 1]
+    compared, complete = compare_traces(tr, {"kind": gtr["kind"][:1], "err": gtr["err"][:1]}, "bf16")
+    assert compared == 3 and complete
+    assert max_abs_rel(x[:1].cpu().numpy(), exp1) <= 2e-2
     ctx.close()
