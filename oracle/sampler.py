@@ -50,27 +50,44 @@ def euler_flow_update(x, v, sigma_t, sigma_next):
     return x + (sigma_next - sigma_t) * v
 
 
+def ddpm_update(x, eps, abar_t, abar_prev, z):
+    """One ancestral sampling step, Eq. 1: x' ~ N(mu, beta I) with
+    mu = (x - (1 - alpha) / sqrt(1 - abar_t) eps) / sqrt(alpha).
+    On a sub-sampled schedule the per-step alpha is the ratio of the two cumulative products,
+    alpha = abar_t / abar_prev, and beta = 1 - alpha (reading: the paper does not spell out the
+    respacing).  `z` is the standard-normal draw, passed in; the caller passes zeros at the final
+    step, which returns the mean (reading: the usual convention, the paper is silent)."""
+    alpha = abar_t / abar_prev
+    beta = 1.0 - alpha
+    mu = (x - beta / np.sqrt(1.0 - abar_t) * eps) / np.sqrt(alpha)
+    return mu + np.sqrt(beta) * z
+
+
 def cfg_combine(out_cond, out_uncond, scale):
     return out_uncond + scale * (out_cond - out_uncond)
 
 
 @dataclass
 class Solver:
-    kind: str                 # "ddim" | "flow"
+    kind: str                 # "ddim" | "flow" | "ddpm"
     timesteps: np.ndarray     # [S] value the model is conditioned on at step s
-    table: np.ndarray         # [S+1] alpha_bar (ddim) or sigma (flow)
+    table: np.ndarray         # [S+1] alpha_bar (ddim, ddpm) or sigma (flow)
     cfg_scale: float = 0.0    # > 0: classifier-free guidance with an extra null-label row
+    noise: Optional[np.ndarray] = None   # ddpm: [S, B, *latent] standard-normal draws (step S-1 is not used)
 
     @property
     def steps(self) -> int:
         return len(self.timesteps)
 
-    def update(self, x, out, s):
+    def update(self, x, out, s, sample=0):
         a, b = float(self.table[s]), float(self.table[s + 1])
         if self.kind == "ddim":
             return ddim_update(x, out, a, b)
         if self.kind == "flow":
             return euler_flow_update(x, out, a, b)
+        if self.kind == "ddpm":
+            z = np.zeros_like(x) if s == self.steps - 1 else np.asarray(self.noise[s][sample], np.float64).reshape(x.shape)
+            return ddpm_update(x, out, a, b, z)
         raise ValueError(self.kind)
 
 
@@ -150,8 +167,9 @@ def speculative_attempt(model, cache: core.FeatureCache, cfg: SpecaConfig, x_row
     return True, errs, model.finish(h, c)
 
 
-def sample_one(model, cfg: SpecaConfig, solver: Solver, tau: np.ndarray, x0: np.ndarray, label):
-    """Whole trajectory of one sample.  x0: [C,(T,)H,W].  -> (final latent, kinds[S], errs[S,rows])."""
+def sample_one(model, cfg: SpecaConfig, solver: Solver, tau: np.ndarray, x0: np.ndarray, label, sample_index: int = 0):
+    """Whole trajectory of one sample.  x0: [C,(T,)H,W].  -> (final latent, kinds[S], errs[S,rows]).
+    sample_index picks the sample's draws out of solver.noise (stochastic solver only)."""
     S = solver.steps
     labels = _rows_for_sample(model, solver, label)
     R = 2 if solver.cfg_scale > 0 else 1
@@ -172,7 +190,7 @@ def sample_one(model, cfg: SpecaConfig, solver: Solver, tau: np.ndarray, x0: np.
             spec = ok
         if not spec:
             out_rows = full_step(model, cache, x_rows, t, labels, s)
-        x = solver.update(x, _model_out(out_rows, solver), s)
+        x = solver.update(x, _model_out(out_rows, solver), s, sample_index)
     return x, kinds, errs
 
 
@@ -184,7 +202,7 @@ def sample(model, cfg: SpecaConfig, solver: Solver, tau: np.ndarray, latents: np
     out = np.empty(latents.shape, dtype=np.float64)
     tr = Trace(np.zeros((B, S), np.int8), np.full((B, S, R), np.nan, np.float32), np.asarray(tau, np.float32))
     for b in range(B):
-        out[b], tr.kind[b], tr.err[b] = sample_one(model, cfg, solver, tr.tau, latents[b], labels[b])
+        out[b], tr.kind[b], tr.err[b] = sample_one(model, cfg, solver, tr.tau, latents[b], labels[b], b)
     return out, tr
 
 
@@ -198,6 +216,6 @@ def sample_plain(model, solver: Solver, latents: np.ndarray, labels: Sequence[in
         R = 2 if solver.cfg_scale > 0 else 1
         for s in range(solver.steps):
             o, _ = model.forward(np.repeat(x[None], R, axis=0), float(solver.timesteps[s]), lab)
-            x = solver.update(x, _model_out(o, solver), s)
+            x = solver.update(x, _model_out(o, solver), s, b)
         out[b] = x
     return out

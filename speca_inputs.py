@@ -186,6 +186,12 @@ def make_latents(batch: int, channels: int, hw: int, seed: int = 0) -> np.ndarra
     return _rng(seed, 2).standard_normal((batch, channels, hw, hw), dtype=np.float32)
 
 
+def make_solver_noise(steps: int, latent_shape: Tuple[int, ...], seed: int = 0) -> np.ndarray:
+    """Standard-normal draws of a stochastic solver, float32 [steps, *latent_shape] (latent_shape
+    starts with the batch).  Both sides of a parity test read the same array."""
+    return _rng(seed, 4).standard_normal((steps,) + tuple(latent_shape), dtype=np.float32)
+
+
 def make_labels(batch: int, num_classes: int, seed: int = 0) -> np.ndarray:
     return _rng(seed, 3).integers(0, num_classes, size=(batch,), dtype=np.int64).astype(np.int32)
 

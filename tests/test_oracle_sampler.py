@@ -147,6 +147,51 @@ def test_ddim_closed_forms():
     np.testing.assert_allclose(sampler.ddim_update(xt, eps, a, 1.0), x0, rtol=1e-12)
 
 
+def test_ddpm_step_pins():
+    """Eq. 1.  Pins: a hand-computed value, the Gaussian posterior mean it must equal when the
+    predicted noise is the true one, the clean end, and the variance of the draw."""
+    # by hand: abar_t = .36, abar_prev = .81 -> alpha = 4/9, beta = 5/9;
+    # mu = (1 - (5/9)/0.8 * 0.5) / (2/3) = 0.9791666..., x' = mu + sqrt(5/9) * 1.2 = 1.8735938...
+    got = sampler.ddpm_update(np.array([1.0]), np.array([0.5]), 0.36, 0.81, np.array([1.2]))
+    np.testing.assert_allclose(got, [0.97916666666666667 + 0.7453559924999299 * 1.2], rtol=1e-14)
+    # true noise: the mean is the posterior mean of q(x_prev | x_t, x0)
+    x0, eps = np.array([0.3, -0.7, 1.9]), np.array([1.1, 0.4, -0.8])
+    a, b = 0.36, 0.81
+    al, be = a / b, 1 - a / b
+    xt = np.sqrt(a) * x0 + np.sqrt(1 - a) * eps
+    post = np.sqrt(b) * be / (1 - a) * x0 + np.sqrt(al) * (1 - b) / (1 - a) * xt
+    np.testing.assert_allclose(sampler.ddpm_update(xt, eps, a, b, 0 * xt), post, rtol=1e-13)
+    # clean end: abar_prev = 1 returns x0, as the deterministic solver does
+    np.testing.assert_allclose(sampler.ddpm_update(xt, eps, a, 1.0, 0 * xt), x0, rtol=1e-13)
+    np.testing.assert_allclose(sampler.ddpm_update(xt, eps, a, 1.0, 0 * xt), sampler.ddim_update(xt, eps, a, 1.0), rtol=1e-13)
+    # no noise level change: nothing moves
+    np.testing.assert_allclose(sampler.ddpm_update(xt, eps, a, a, xt), xt, rtol=1e-15)
+    # the draw enters with standard deviation sqrt(beta), not beta
+    z = np.random.default_rng(0).standard_normal(200000)
+    d = sampler.ddpm_update(np.zeros_like(z), np.zeros_like(z), a, b, z)
+    assert abs(d.var() / be - 1) < 0.01 and abs(d.mean()) < 0.01
+
+
+def test_ddpm_trajectory_uses_each_samples_draws(tiny):
+    s, m, _, lat, lab = tiny
+    ts, ab = si.ddim_tables(6)
+    noise = si.make_solver_noise(6, lat.shape, 0)
+    sol = sampler.Solver("ddpm", ts, ab, noise=noise)
+    plain = sampler.sample_plain(m, sol, lat, lab)
+    out, tr = sampler.sample(m, sampler.SpecaConfig(order=1, interval=3), sol, np.zeros(6, np.float32), lat, lab)
+    assert np.array_equal(out, plain)
+    # the final step adds no noise; every earlier draw matters, per sample
+    n2 = noise.copy(); n2[5] += 1.0
+    assert np.array_equal(sampler.sample_plain(m, sampler.Solver("ddpm", ts, ab, noise=n2), lat, lab), plain)
+    n3 = noise.copy(); n3[4, 1] += 1.0
+    o3 = sampler.sample_plain(m, sampler.Solver("ddpm", ts, ab, noise=n3), lat, lab)
+    assert np.array_equal(o3[0], plain[0]) and not np.array_equal(o3[1], plain[1])
+    # zero draws: one step of it equals its own mean, and differs from the deterministic solver
+    z0 = sampler.sample_plain(m, sampler.Solver("ddpm", ts, ab, noise=0 * noise), lat, lab)
+    dd = sampler.sample_plain(m, sampler.Solver("ddim", ts, ab), lat, lab)
+    assert np.all(np.isfinite(z0)) and not np.allclose(z0, dd)
+
+
 def test_flow_and_cfg_closed_forms():
     ts, sig = si.flow_tables(10)
     x = np.array([1.0, 2.0]); v = np.array([0.5, -1.0])
