@@ -51,7 +51,7 @@ typedef enum speca_status {
 enum { SPECA_F32 = 0, SPECA_BF16 = 1 };                       /* storage types */
 enum { SPECA_MODEL_NONE = 0, SPECA_MODEL_DIT = 1, SPECA_MODEL_MMDIT = 2 };
 enum { SPECA_COEF_TAYLOR = 0, SPECA_COEF_NEWTON = 1, SPECA_COEF_ADAMS_BASHFORTH = 2 };
-enum { SPECA_SOLVER_DDIM = 0, SPECA_SOLVER_FLOW = 1 };
+enum { SPECA_SOLVER_DDIM = 0, SPECA_SOLVER_FLOW = 1, SPECA_SOLVER_DDPM = 2 };
 enum { SPECA_KIND_FULL = 0, SPECA_KIND_SPEC = 1, SPECA_KIND_REJECT = 2 };
 enum { SPECA_METRIC_L2 = 0, SPECA_METRIC_L1 = 1, SPECA_METRIC_LINF = 2, SPECA_METRIC_COSINE = 3 };
 
@@ -115,11 +115,18 @@ typedef struct speca_cond {
 
 /* Solver tables are data (the method is independent of the noise schedule). */
 typedef struct speca_solver {
-  int32_t kind;            /* SPECA_SOLVER_DDIM (eta = 0) | SPECA_SOLVER_FLOW (Euler) */
+  int32_t kind;            /* SPECA_SOLVER_DDIM (eta = 0) | SPECA_SOLVER_FLOW (Euler) | SPECA_SOLVER_DDPM (Eq. 1) */
   int32_t steps;           /* S */
   const float* timesteps;  /* HOST [S]   conditioning value of step s */
-  const float* table;      /* HOST [S+1] alpha_bar (DDIM; last entry 1) or sigma (flow; last entry 0) */
+  const float* table;      /* HOST [S+1] alpha_bar (DDIM, DDPM; last entry 1) or sigma (flow; last entry 0) */
   float cfg_scale;         /* > 0: classifier-free guidance, rows = 2 x batch, null label for the second half */
+  const float* noise;      /* DEVICE fp32 [S][batch, C, (T,) H, W]: the standard-normal draws of DDPM (the library
+                            * draws nothing itself, so a trajectory is a function of its inputs); step S-1 is not
+                            * read.  Ignored by the other solvers; NULL with DDPM is SPECA_EINVAL.
+                            * DDPM step, Eq. 1 on the given (possibly sub-sampled) schedule:
+                            *   alpha = table[s] / table[s+1], beta = 1 - alpha,
+                            *   x <- (x - beta / sqrt(1 - table[s]) * e) / sqrt(alpha) + sqrt(beta) * noise[s];
+                            * the final step returns the mean. */
 } speca_solver;
 
 /* Per-sample, per-step record of speca_sample.  All HOST memory owned by the caller;

@@ -16,7 +16,7 @@ OK, EINVAL, ENOMEM, ESTATE, EHIP, EUNSUPPORTED = range(6)
 F32, BF16 = 0, 1
 MODEL_NONE, MODEL_DIT, MODEL_MMDIT = 0, 1, 2
 COEF_TAYLOR, COEF_NEWTON, COEF_ADAMS_BASHFORTH = 0, 1, 2
-SOLVER_DDIM, SOLVER_FLOW = 0, 1
+SOLVER_DDIM, SOLVER_FLOW, SOLVER_DDPM = 0, 1, 2
 KIND_FULL, KIND_SPEC, KIND_REJECT = 0, 1, 2
 METRIC_L2, METRIC_L1, METRIC_LINF, METRIC_COSINE = 0, 1, 2, 3
 MAX_ORDER = 4
@@ -55,7 +55,7 @@ class Cond(C.Structure):
 
 class Solver(C.Structure):
     _fields_ = [("kind", C.c_int32), ("steps", C.c_int32), ("timesteps", C.POINTER(C.c_float)),
-                ("table", C.POINTER(C.c_float)), ("cfg_scale", C.c_float)]
+                ("table", C.POINTER(C.c_float)), ("cfg_scale", C.c_float), ("noise", C.c_void_p)]
 
 
 class Trace(C.Structure):
@@ -364,13 +364,17 @@ class Context:
         return err, acc.astype(bool)
 
     def sample(self, latents, timesteps, table, tau, solver_kind=SOLVER_DDIM, cfg_scale: float = 0.0, labels=None,
-               txt=None, pooled=None, want_trace: bool = True):
-        """latents: fp32 device tensor [B, ...], updated in place.  -> dict trace."""
+               txt=None, pooled=None, want_trace: bool = True, noise=None):
+        """latents: fp32 device tensor [B, ...], updated in place.  noise: fp32 device tensor [S, B, ...]
+        (SOLVER_DDPM).  -> dict trace."""
         B = latents.shape[0]
         ts, tb, ta = _f32(timesteps), _f32(table), _f32(tau)
         S = len(ts)
         assert len(tb) == S + 1 and len(ta) == S
-        sol = Solver(solver_kind, S, _p(ts, C.c_float), _p(tb, C.c_float), float(cfg_scale))
+        if noise is not None:
+            assert noise.is_contiguous() and tuple(noise.shape) == (S,) + tuple(latents.shape) and noise.dtype == latents.dtype
+        sol = Solver(solver_kind, S, _p(ts, C.c_float), _p(tb, C.c_float), float(cfg_scale),
+                     C.c_void_p(noise.data_ptr()) if noise is not None else None)
         c, keep = self._cond(labels, 0.0, txt, pooled)
         kind = np.zeros((B, S), np.int8); err = np.full((B, S, 2), np.nan, np.float32)
         tr = Trace(_p(kind, C.c_int8), _p(err, C.c_float), 0, 0, 0)

@@ -40,6 +40,6 @@ Error make_mmdit_model(const speca_model_desc& d, const speca_weights* w, std::u
 // Solver update on device (DDIM eta=0 or flow Euler) with optional guidance combine.
 // latents [batch][n] fp32; model_out [rows][n] fp32, rows = batch or 2*batch.
 Error launch_solver_update(int kind, float* latents, const float* model_out, int batch, int64_t n, float cfg_scale,
-                           float tab_s, float tab_next, hipStream_t st);
+                           float tab_s, float tab_next, const float* draws, hipStream_t st);
 
 }  // namespace speca

@@ -14,10 +14,11 @@ namespace {
 
 // DDIM (eta = 0):  x0 = (x - sqrt(1-a) e)/sqrt(a);  x' = sqrt(a') x0 + sqrt(1-a') e
 // flow Euler:      x' = x + (sigma' - sigma) v
+// DDPM (Eq. 1):    al = a/a', be = 1 - al;  x' = (x - be/sqrt(1-a) e)/sqrt(al) + sqrt(be) z  (z = nullptr: the mean)
 // Guidance:        e = e_u + scale (e_c - e_u), conditional rows first, unconditional rows after.
 __global__ __launch_bounds__(256) void solver_update_kernel(int kind, float* __restrict__ x, const float* __restrict__ out,
                                                             int64_t total, int64_t uncond_offset, float cfg_scale, float ta,
-                                                            float tb) {
+                                                            float tb, const float* __restrict__ z) {
   const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   if (i >= total) return;
   float e = out[i];
@@ -30,8 +31,12 @@ __global__ __launch_bounds__(256) void solver_update_kernel(int kind, float* __r
   if (kind == SPECA_SOLVER_DDIM) {
     const float x0 = (xv - sqrtf(1.0f - ta) * e) / sqrtf(ta);
     r = sqrtf(tb) * x0 + sqrtf(1.0f - tb) * e;
-  } else {
+  } else if (kind == SPECA_SOLVER_FLOW) {
     r = xv + (tb - ta) * e;
+  } else {
+    const float al = ta / tb, be = 1.0f - al;
+    r = (xv - be / sqrtf(1.0f - ta) * e) / sqrtf(al);
+    if (z) r += sqrtf(be) * z[i];
   }
   x[i] = r;
 }
@@ -39,12 +44,12 @@ __global__ __launch_bounds__(256) void solver_update_kernel(int kind, float* __r
 }  // namespace
 
 Error launch_solver_update(int kind, float* latents, const float* model_out, int batch, int64_t n, float cfg_scale, float tab_s,
-                           float tab_next, hipStream_t st) {
+                           float tab_next, const float* draws, hipStream_t st) {
   const int64_t total = static_cast<int64_t>(batch) * n;
   const int64_t blocks = (total + 255) / 256;
   if (blocks > 0x7FFFFFFF) SPECA_FAIL(SPECA_EINVAL, "latent too large for one launch");
   solver_update_kernel<<<static_cast<unsigned>(blocks), 256, 0, st>>>(kind, latents, model_out, total, total, cfg_scale, tab_s,
-                                                                     tab_next);
+                                                                     tab_next, draws);
   SPECA_HIP(hipGetLastError());
   return ok();
 }
@@ -54,7 +59,9 @@ Error sample_impl(speca_ctx* ctx, float* latents, int batch, const speca_cond* c
   if (!ctx->model) SPECA_FAIL(SPECA_EUNSUPPORTED, "this context has no model (cache-only)");
   if (!ctx->cache_ready) SPECA_FAIL(SPECA_ESTATE, "speca_init_cache has not been called");
   if (!latents || !cond || !solver || !tau) SPECA_FAIL(SPECA_EINVAL, "latents, cond, solver and tau must not be NULL");
-  if (solver->kind != SPECA_SOLVER_DDIM && solver->kind != SPECA_SOLVER_FLOW) SPECA_FAIL(SPECA_EINVAL, "solver kind = %d", solver->kind);
+  if (solver->kind != SPECA_SOLVER_DDIM && solver->kind != SPECA_SOLVER_FLOW && solver->kind != SPECA_SOLVER_DDPM)
+    SPECA_FAIL(SPECA_EINVAL, "solver kind = %d", solver->kind);
+  if (solver->kind == SPECA_SOLVER_DDPM && !solver->noise) SPECA_FAIL(SPECA_EINVAL, "the DDPM solver needs solver->noise");
   if (solver->steps < 1 || !solver->timesteps || !solver->table) SPECA_FAIL(SPECA_EINVAL, "solver tables missing");
   if (batch < 1) SPECA_FAIL(SPECA_EINVAL, "batch = %d", batch);
   const bool guided = solver->cfg_scale > 0.0f;
@@ -140,9 +147,10 @@ Error sample_impl(speca_ctx* ctx, float* latents, int batch, const speca_cond* c
         for (size_t i = 0; i < ns; ++i) rows.push_back(B + todo[i0 + i]);
       SPECA_TRY(ctx->model->full_step(ctx, latents, B, &c, labels.data(), s, rows.data(), static_cast<int>(rows.size()), model_out));
     }
-    ProfScope ps(ctx, SPECA_PROF_OTHER, 0.0, static_cast<double>(B) * n * 4 * (2 + R));
+    const float* draws = solver->kind == SPECA_SOLVER_DDPM && s + 1 < S ? solver->noise + static_cast<int64_t>(s) * B * n : nullptr;
+    ProfScope ps(ctx, SPECA_PROF_OTHER, 0.0, static_cast<double>(B) * n * 4 * (2 + R + (draws ? 1 : 0)));
     SPECA_TRY(launch_solver_update(solver->kind, latents, model_out, B, n, guided ? solver->cfg_scale : 0.0f, solver->table[s],
-                                   solver->table[s + 1], ctx->stream));
+                                   solver->table[s + 1], draws, ctx->stream));
     if (trace) {
       for (int b = 0; b < B; ++b) {
         if (trace->kind) trace->kind[static_cast<int64_t>(b) * S + s] = kinds[b];

@@ -104,19 +104,22 @@ def test_spec_step_matches_oracle(tiny):
         assert acc2.tolist() == [e <= mid for e in exp_e]
 
 
-def _run_both(s, om, ctx, S, B, cfg_kwargs, tau, cfg_scale=0.0, seed=0):
+def _run_both(s, om, ctx, S, B, cfg_kwargs, tau, cfg_scale=0.0, seed=0, solver="ddim"):
     import paper_2509_11628_amd as sp
     from paper_2509_11628_amd import binding as bd
     ts, ab = si.ddim_tables(S)
     lat = si.make_latents(B, s.in_channels, s.latent_hw, seed)
     lab = si.make_labels(B, s.num_classes, seed)
-    sol = osamp.Solver("ddim", ts, ab, cfg_scale)
+    noise = si.make_solver_noise(S, lat.shape, seed) if solver == "ddpm" else None
+    sol = osamp.Solver(solver, ts, ab, cfg_scale, noise)
     exp, tr = osamp.sample(om, osamp.SpecaConfig(cache_store="bf16" if s.dtype == "bf16" else None, **cfg_kwargs), sol, tau, lat, lab)
     mode = {"newton": bd.COEF_NEWTON, "adams_bashforth": bd.COEF_ADAMS_BASHFORTH}.get(cfg_kwargs.get("mode"), bd.COEF_TAYLOR)
     kw = {k: v for k, v in cfg_kwargs.items() if k != "mode"}
     ctx.init_cache(sp.make_cfg(coef_mode=mode, **kw), B * (2 if cfg_scale > 0 else 1))
     xd = torch.from_numpy(lat).cuda()
-    got = ctx.sample(xd, ts, ab, tau, cfg_scale=cfg_scale, labels=lab)
+    got = ctx.sample(xd, ts, ab, tau, cfg_scale=cfg_scale, labels=lab,
+                     solver_kind=bd.SOLVER_DDPM if solver == "ddpm" else bd.SOLVER_DDIM,
+                     noise=torch.from_numpy(noise).cuda() if noise is not None else None)
     return exp, tr, xd.cpu().numpy(), got
 
 
@@ -229,6 +232,28 @@ def test_guided_trajectory(tiny):
         np.testing.assert_allclose(gtr["err"][m], tr.err[m], rtol=1e-3 if s.dtype == "f32" else 1.5e-1, atol=0 if s.dtype == "f32" else 5e-3)
 
 
+def test_stochastic_solver_trajectory(tiny):
+    """Eq. 1 as the solver: the draws are an input, so the trajectory is still a function of its
+    inputs and is compared decision by decision; also guided, and with tau = 0 (plain ancestral
+    sampling)."""
+    s, w, om, ctx = tiny
+    tau = core.tau_linear(0.08, 0.02, 12)
+    for kw, scale in ((dict(order=1, interval=4), 0.0), (dict(order=2, interval=3), 1.5)):
+        exp, tr, got, gtr = _run_both(s, om, ctx, 12, 2, kw, tau, cfg_scale=scale, seed=3, solver="ddpm")
+        compared, complete = compare_traces(tr, gtr, s.dtype)
+        print(f"\n[{s.dtype}] ancestral: kinds {tr.kind.tolist()} compared {compared} complete {complete}")
+        assert compared >= 4
+        if s.dtype == "f32":
+            assert complete
+        if complete:
+            assert max_abs_rel(got, exp) <= _tol(s)
+    exp, tr, got, gtr = _run_both(s, om, ctx, 12, 2, dict(order=1, interval=4), np.zeros(12, np.float32), seed=3, solver="ddpm")
+    assert np.all(gtr["kind"] == 0) and max_abs_rel(got, exp) <= _tol(s)
+    # the draws do reach the latents: the deterministic solver lands elsewhere
+    _, _, got_ddim, _ = _run_both(s, om, ctx, 12, 2, dict(order=1, interval=4), np.zeros(12, np.float32), seed=3)
+    assert max_abs_rel(got, got_ddim) > 0.05
+
+
 def test_sample_error_paths(tiny):
     import paper_2509_11628_amd as sp
     from paper_2509_11628_amd import binding as bd
@@ -244,6 +269,10 @@ def test_sample_error_paths(tiny):
     assert e.value.code == bd.EINVAL
     with pytest.raises(sp.SpecaError) as e:
         ctx.init_cache(sp.make_cfg(order=1, interval=2, verify_block=5), 2)
+    assert e.value.code == bd.EINVAL
+    ctx.init_cache(sp.make_cfg(order=1, interval=2), 2)
+    with pytest.raises(sp.SpecaError) as e:
+        ctx.sample(x, ts, ab, np.ones(4, np.float32), labels=[0, 1], solver_kind=bd.SOLVER_DDPM)     # no draws given
     assert e.value.code == bd.EINVAL
 
 
