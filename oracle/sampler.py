@@ -100,6 +100,7 @@ class SpecaConfig:
     eps: float = core.EPS_DEFAULT
     warmup_full: int = 1           # steps 0..warmup_full-1 are always full
     cache_store: Optional[str] = None   # None (float64) | "f32" | "bf16": storage rounding of the cache
+    cache_layout: str = "differences"   # "differences" (Sec. 3.3 as described) | "ring" (raw features, same forecasts)
 
 
 @dataclass
@@ -173,7 +174,7 @@ def sample_one(model, cfg: SpecaConfig, solver: Solver, tau: np.ndarray, x0: np.
     S = solver.steps
     labels = _rows_for_sample(model, solver, label)
     R = 2 if solver.cfg_scale > 0 else 1
-    cache = core.FeatureCache(model.n_slots, cfg.order, cfg.mode, cfg.cache_store)
+    cache = core.make_cache(cfg.cache_layout, model.n_slots, cfg.order, cfg.mode, cfg.cache_store)
     x = np.asarray(x0, dtype=np.float64)
     kinds = np.zeros(S, dtype=np.int8)
     errs = np.full((S, R), np.nan, dtype=np.float32)

@@ -134,6 +134,69 @@ class FeatureCache:
         return acc
 
 
+class RingFeatureCache:
+    """The same cache kept as raw features: for every slot the features of the last m+1 full
+    steps (each rounded once to the storage type), and no differences.  The differences of
+    Eq. 3 are formed when a forecast is asked for, by the recursion's own definition
+        D^0_j = F_j,   D^i_j = (D^{i-1}_j - D^{i-1}_{j+1}) / d_i(j),
+    where j counts references backwards from the latest and d_i(j) is the divisor the
+    difference layout used when reference j was taken (taylor, adams_bashforth: the gap
+    r_j - r_{j+1}; newton: r_j - r_{j+i}).  In exact arithmetic this is the forecast of
+    FeatureCache; the two differ only in what is rounded to the storage type (the features
+    here, the differences there).  Same interface as FeatureCache."""
+
+    def __init__(self, n_slots: int, order: int, mode: str = "taylor", store: Optional[str] = None):
+        assert order >= 0 and mode in ("taylor", "newton", "adams_bashforth")
+        self.n_slots, self.m, self.mode = n_slots, order, mode
+        self.round = storage_rounder(store)
+        self.F: List[List[np.ndarray]] = [[] for _ in range(n_slots)]      # latest first, at most m+1 each
+        self.refs: List[int] = []
+
+    @property
+    def order_available(self) -> int:
+        return min(self.m, len(self.refs) - 1)
+
+    def refresh(self, step: int, feats: Sequence[np.ndarray]) -> None:
+        assert len(feats) == self.n_slots
+        assert not self.refs or step > self.refs[0]
+        for j in range(self.n_slots):
+            self.F[j] = [self.round(np.asarray(feats[j], dtype=np.float64))] + self.F[j][: self.m]
+        self.refs = [step] + self.refs[: self.m]
+
+    def coefficients(self, step: int) -> List[float]:
+        return forecast_coefficients(self.mode, step, self.refs, self.order_available)
+
+    def differences(self, slot: int) -> List[np.ndarray]:
+        """D^0 .. D^order at the latest reference, float64."""
+        r, o = self.refs, self.order_available
+        level = list(self.F[slot][: o + 1])                 # D^0_j for j = 0..o
+        out = [level[0]]
+        for i in range(1, o + 1):
+            nxt = []
+            for j in range(len(level) - 1):
+                d = (r[j] - r[j + i]) if self.mode == "newton" else (r[j] - r[j + 1])
+                nxt.append((level[j] - level[j + 1]) / float(d))
+            level = nxt
+            out.append(level[0])
+        return out
+
+    def forecast(self, step: int, slot: int) -> np.ndarray:
+        c = self.coefficients(step)
+        D = self.differences(slot)
+        acc = np.zeros_like(D[0])
+        for i, ci in enumerate(c):
+            acc = acc + ci * D[i]
+        return acc
+
+
+def make_cache(layout: str, n_slots: int, order: int, mode: str = "taylor", store: Optional[str] = None):
+    if layout == "differences":
+        return FeatureCache(n_slots, order, mode, store)
+    if layout == "ring":
+        return RingFeatureCache(n_slots, order, mode, store)
+    raise ValueError(layout)
+
+
 def forecast_coefficients(mode: str, step: int, refs: Sequence[int], order: int) -> List[float]:
     """Weights c_i of the cached differences in the forecast for ``step``.
 

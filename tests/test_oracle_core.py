@@ -279,3 +279,56 @@ def test_adams_bashforth_exact_on_lines_and_differs_from_taylor_on_curves():
     assert ab.forecast(9, 0)[0] == 80.0 and ty.forecast(9, 0)[0] == 77.0
     assert core.forecast_coefficients("adams_bashforth", 9, [8, 4, 0], 2) == [1.0, 1.0, 2.0]
     assert core.forecast_coefficients("adams_bashforth", 9, [8], 0) == [1.0]
+
+
+# --- raw-feature ring layout of the cache -----------------------------------------------------
+
+
+@pytest.mark.parametrize("mode", ["taylor", "newton", "adams_bashforth"])
+@pytest.mark.parametrize("m", [0, 1, 2, 3, 4])
+def test_ring_layout_gives_the_forecasts_of_the_difference_layout(mode, m):
+    """Irregular reference steps, more of them than the ring keeps, forecasts asked for during the
+    warm-up too: the two layouts agree to rounding when nothing is rounded for storage."""
+    rng = np.random.default_rng(11 * m + len(mode))
+    steps = [0, 3, 4, 9, 11, 16, 17, 22]
+    diff = core.FeatureCache(2, m, mode); ring = core.make_cache("ring", 2, m, mode)
+    for n, s in enumerate(steps):
+        f = [rng.standard_normal((3, 4)), rng.standard_normal((3, 4))]
+        diff.refresh(s, f); ring.refresh(s, f)
+        assert ring.refs == diff.refs and ring.order_available == diff.order_available
+        assert len(ring.F[0]) == min(m + 1, n + 1)
+        for k in (1, 2, 4):
+            for slot in (0, 1):
+                np.testing.assert_allclose(ring.forecast(s + k, slot), diff.forecast(s + k, slot), rtol=1e-10, atol=1e-10)
+
+
+def test_ring_layout_uniform_grid_is_eq2_written_out():
+    m, N = 2, 5
+    rng = np.random.default_rng(0)
+    raw = [rng.standard_normal(7) for _ in range(5)]
+    ring = core.make_cache("ring", 1, m, "taylor")
+    for j, f in enumerate(raw):
+        ring.refresh(j * N, [f])
+    for k in range(1, N):
+        np.testing.assert_allclose(ring.forecast(ring.refs[0] + k, 0), core.taylor_forecast_eq2(raw[::-1], N, k, m),
+                                   rtol=1e-11, atol=1e-11)
+
+
+def test_ring_layout_newton_reproduces_polynomials_and_rounds_features_only():
+    # degree-3 polynomial sampled at irregular steps: order 3 divided differences extrapolate it exactly
+    poly = lambda u: np.array([0.5 * u ** 3 - 2.0 * u ** 2 + u - 7.0, u ** 2])
+    ring = core.make_cache("ring", 1, 3, "newton")
+    for s in (1, 2, 5, 7, 12):
+        ring.refresh(s, [poly(float(s))])
+    np.testing.assert_allclose(ring.forecast(15, 0), poly(15.0), rtol=1e-12)
+    # storage rounding applies to the features (and to nothing else)
+    rb = core.make_cache("ring", 1, 2, "taylor", "bf16")
+    f = np.array([1.2345678, -3.3333333])
+    rb.refresh(0, [f]); rb.refresh(2, [2 * f])
+    from speca_inputs import round_to_bf16
+    assert np.array_equal(rb.F[0][0], round_to_bf16(2 * f).astype(np.float64))
+    assert np.array_equal(rb.F[0][1], round_to_bf16(f).astype(np.float64))
+    a, b = rb.F[0][0], rb.F[0][1]
+    np.testing.assert_allclose(rb.forecast(3, 0), a + 0.5 * (a - b), rtol=1e-15)
+    with pytest.raises(ValueError):
+        core.make_cache("rings", 1, 1)
