@@ -75,7 +75,7 @@ def bench_forecast(args):
     from paper_2509_11628_amd import binding as bd
     slots, B, T, D, m = 28, 8, 256, 1152, 2
     ctx = sp.Context(sp.cache_only_desc(slots, T, D, bd.BF16))
-    ctx.init_cache(sp.make_cfg(order=m, interval=4), B)
+    ctx.init_cache(sp.make_cfg(order=m, interval=4, layout=_layout(args)), B)
     rows = list(range(B))
     for s_, f in zip([0, 4, 8], si.feature_trajectory(slots, B, T, D, [0, 4, 8], seed=0, dtype="bf16")):
         ctx.refresh(s_, rows, torch.from_numpy(f).cuda().bfloat16())
@@ -108,7 +108,7 @@ def bench_forecast(args):
     if not args.no_cpu_baseline:
         from oracle import speca_core as core
         feats = si.feature_trajectory(1, 1, T, D, [0, 4, 8], seed=0, dtype="bf16")
-        c = core.FeatureCache(1, m, "taylor", "bf16")
+        c = core.make_cache(args.layout, 1, m, "taylor", "bf16")
         for s_, f in zip([0, 4, 8], feats):
             c.refresh(s_, [f[0, 0]])
         t1 = time.perf_counter()
@@ -192,7 +192,7 @@ def bench_mmdit(args, which):
     w = device_mmdit_weights(shape)
     ctx = sp.Context(sp.mmdit_desc(shape), w)
     order = 2
-    ctx.init_cache(sp.make_cfg(order=order, interval=args.interval), 1)
+    ctx.init_cache(sp.make_cfg(order=order, interval=args.interval, layout=_layout(args)), 1)
     lat = si.make_video_latents(1, shape, 0)
     txt, vec = si.make_text(1, shape, 0)
     td, vd = torch.from_numpy(txt).cuda().bfloat16(), torch.from_numpy(vec).cuda().bfloat16()
@@ -241,7 +241,7 @@ def bench_mmdit(args, which):
         "config": {"workload": ("config 4: FLUX-shaped MMDiT 1024x1024" if which == "flux" else "config 5: HunyuanVideo-shaped MMDiT 480p 2s")
                    + ", bf16, batch 1, Euler, Taylor order 2", "tokens": shape.tokens, "hidden": shape.hidden,
                    "blocks": [shape.depth_dual, shape.depth_single], "order": order, "interval": args.interval, "tau0": args.tau0,
-                   "tau_end": args.tau_end, "parallelism": "single GPU"},
+                   "tau_end": args.tau_end, "cache_layout": args.layout, "parallelism": "single GPU"},
         "roofline": roof, "cpu_baseline": None,
         "extras": {"images_per_s": 1.0 / dt, "accept_rate": tr["n_spec"] / float(K), "n_full": tr["n_full"], "n_spec": tr["n_spec"],
                    "n_reject": tr["n_reject"], "errors": [None if np.isnan(e) else float(e) for e in tr["err"][0, :, 0]],
@@ -255,6 +255,11 @@ def bench_mmdit(args, which):
     print(json.dumps(out))
 
 
+def _layout(args):
+    from paper_2509_11628_amd import binding as bd
+    return bd.CACHE_RING if args.layout == "ring" else bd.CACHE_DIFFERENCES
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", choices=["dit_xl2", "forecast", "copy", "flux", "hunyuan"], default="dit_xl2")
@@ -265,6 +270,8 @@ def main():
     ap.add_argument("--tau0", type=float, default=0.1)
     ap.add_argument("--tau-end", type=float, default=0.02)
     ap.add_argument("--interval", type=int, default=5)
+    ap.add_argument("--layout", choices=["differences", "ring"], default="ring",
+                    help="what the cache planes hold: the differences of Eq. 3, or the raw features of the last m+1 full steps")
     ap.add_argument("--lanes", type=int, default=4, help="row groups of a step that run side by side (1 = serial)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -290,7 +297,7 @@ def main():
     B, cfg_scale, order = 8, 1.5, 2
     weights = si.make_dit_weights(shape, 0)
     ctx = sp.Context(sp.dit_desc(shape), sp.to_device(weights, bd.BF16))
-    ctx.init_cache(sp.make_cfg(order=order, interval=args.interval), 2 * B)
+    ctx.init_cache(sp.make_cfg(order=order, interval=args.interval, layout=_layout(args)), 2 * B)
     ctx.set_lanes(args.lanes)          # the event-profiled pass below always runs serially (clean per-kernel times)
     lat = si.make_latents(B, shape.in_channels, shape.latent_hw, 0)
     lab = si.make_labels(B, shape.num_classes, 0)
@@ -376,7 +383,7 @@ def main():
         "config": {"workload": "config 3: DiT-XL/2-shaped bf16, batch 8 x CFG 1.5 (16 rows), 256 tokens, DDIM, Taylor order 2",
                    "global_batch": B, "rows": 2 * B, "tokens": shape.tokens, "hidden": shape.hidden, "blocks": shape.depth,
                    "order": order, "interval": args.interval, "tau0": args.tau0, "tau_end": args.tau_end, "lanes": args.lanes,
-                   "parallelism": "single GPU"},
+                   "cache_layout": args.layout, "parallelism": "single GPU"},
         "roofline": roof,
         "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(shape, weights),
         "extras": extras,

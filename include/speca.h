@@ -54,6 +54,13 @@ enum { SPECA_COEF_TAYLOR = 0, SPECA_COEF_NEWTON = 1, SPECA_COEF_ADAMS_BASHFORTH 
 enum { SPECA_SOLVER_DDIM = 0, SPECA_SOLVER_FLOW = 1, SPECA_SOLVER_DDPM = 2 };
 enum { SPECA_KIND_FULL = 0, SPECA_KIND_SPEC = 1, SPECA_KIND_REJECT = 2 };
 enum { SPECA_METRIC_L2 = 0, SPECA_METRIC_L1 = 1, SPECA_METRIC_LINF = 2, SPECA_METRIC_COSINE = 3 };
+/* What the m+1 planes of a cache slot hold.  DIFFERENCES: D^0 .. D^m of Eq. 3, updated by the recursion at
+ * every full step (the layout Sec. 3.3 describes).  RING: the features of the last m+1 full steps, each stored
+ * once and never re-read by a refresh; the differences are linear in them, so a forecast (Eq. 2) is a weighted
+ * sum of the planes with weights the host derives from the same recursion (speca_ring_weights).  Both give
+ * the same forecasts in exact arithmetic; they differ in what is rounded to the cache type (differences /
+ * features) and in refresh traffic (reads m, writes m+1 planes / writes one). */
+enum { SPECA_CACHE_DIFFERENCES = 0, SPECA_CACHE_RING = 1 };
 
 #define SPECA_MAX_ORDER 4          /* highest Taylor order m the cache can hold */
 #define SPECA_MAX_LAUNCH_ROWS 64   /* rows handled by one internal launch; larger lists are chunked */
@@ -103,6 +110,7 @@ typedef struct speca_cfg {
   float   eps;             /* Eq. 4 epsilon, paper value 1e-8 */
   int32_t warmup_full;     /* steps 0..warmup_full-1 are always full (>= 1) */
   int32_t metric;          /* SPECA_METRIC_*; L2 is Eq. 4 */
+  int32_t layout;          /* SPECA_CACHE_DIFFERENCES (Sec. 3.3 as described) | SPECA_CACHE_RING */
 } speca_cfg;
 
 /* Conditioning of one call. */
@@ -156,7 +164,9 @@ const char* speca_last_error(const speca_ctx* ctx);
  * May be called again to start a new trajectory.  Sec. 3.3 (features + differences). */
 int speca_init_cache(speca_ctx* ctx, const speca_cfg* cfg, int batch_rows);
 
-/* Cache refresh from materialised features (the cache-only form of a reference step):
+/* (With cfg.layout = SPECA_CACHE_RING the planes hold raw features: speca_refresh stores F into the row's
+ * next plane and nothing else; speca_forecast and every fused path weight the planes accordingly.)
+ * Cache refresh from materialised features (the cache-only form of a reference step):
  * features is DEVICE [n_slots][n_rows][tokens][hidden] in the cache dtype, row i of it
  * belongs to cache row rows[i] (HOST, strictly increasing).  For every listed row stores
  * D0 <- F and D^i <- (D^{i-1}_new - D^{i-1}_old) / d_i, i <= min(m, #references so far),
@@ -276,6 +286,14 @@ int speca_tau_linear(float tau_start, float tau_end, int steps, float* tau_out);
 int speca_coefficients(int coef_mode, int step, const int32_t* refs, int n_refs, int order, float* c_out);
 /* Refresh divisors d[1..order] written to d_out[0..order-1]. */
 int speca_divisors(int coef_mode, int step, const int32_t* refs, int n_refs, int order, float* d_out);
+
+/* RING layout: weights of the stored features in the forecast for `step`, after full steps at
+ * full_steps[0..n_full) (increasing) with a cache of order `order`.  w_out[j] multiplies the feature of age j
+ * (0 = latest), plane_out[j] is the cache plane that holds it; *n_out = features held (<= order+1).  The
+ * weights are sum_i c_i W[i][j], where D^i = sum_j W[i][j] F(age j) follows the refresh recursion of the
+ * chosen policy (Eq. 3 with the divisors of speca_divisors). */
+int speca_ring_weights(int coef_mode, int order, const int32_t* full_steps, int n_full, int step, float* w_out, int32_t* plane_out,
+                       int* n_out);
 
 /* The per-sample schedule state machine of speca_sample, exposed for host-side testing.
  * plan: fills spec_out / full_out (HOST, capacity batch) with the samples to attempt

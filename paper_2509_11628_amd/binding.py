@@ -17,6 +17,7 @@ F32, BF16 = 0, 1
 MODEL_NONE, MODEL_DIT, MODEL_MMDIT = 0, 1, 2
 COEF_TAYLOR, COEF_NEWTON, COEF_ADAMS_BASHFORTH = 0, 1, 2
 SOLVER_DDIM, SOLVER_FLOW, SOLVER_DDPM = 0, 1, 2
+CACHE_DIFFERENCES, CACHE_RING = 0, 1
 KIND_FULL, KIND_SPEC, KIND_REJECT = 0, 1, 2
 METRIC_L2, METRIC_L1, METRIC_LINF, METRIC_COSINE = 0, 1, 2, 3
 MAX_ORDER = 4
@@ -45,7 +46,7 @@ class Weights(C.Structure):
 class Cfg(C.Structure):
     _fields_ = [("order", C.c_int32), ("interval", C.c_int32), ("verify_block", C.c_int32),
                 ("coef_mode", C.c_int32), ("eps", C.c_float), ("warmup_full", C.c_int32),
-                ("metric", C.c_int32)]
+                ("metric", C.c_int32), ("layout", C.c_int32)]
 
 
 class Cond(C.Structure):
@@ -104,6 +105,7 @@ def load_library() -> C.CDLL:
         "speca_tau_linear": [C.c_float, C.c_float, C.c_int, f32p],
         "speca_coefficients": [C.c_int, C.c_int, i32p, C.c_int, C.c_int, f32p],
         "speca_divisors": [C.c_int, C.c_int, i32p, C.c_int, C.c_int, f32p],
+        "speca_ring_weights": [C.c_int, C.c_int, i32p, C.c_int, C.c_int, f32p, i32p, C.POINTER(C.c_int)],
         "speca_sched_create": [C.POINTER(vp), C.c_int, C.POINTER(Cfg)],
         "speca_sched_destroy": [vp],
         "speca_sched_plan": [vp, C.c_int, C.c_float, i32p, C.POINTER(C.c_int), i32p, C.POINTER(C.c_int)],
@@ -124,7 +126,7 @@ EXPORTED = ["speca_create", "speca_destroy", "speca_last_error", "speca_init_cac
             "speca_full_step", "speca_forecast", "speca_verify", "speca_spec_step", "speca_sample",
             "speca_linear", "speca_attention", "speca_set_lanes", "speca_profile_begin", "speca_profile_end",
             "speca_tau_geometric", "speca_tau_linear", "speca_coefficients", "speca_divisors",
-            "speca_sched_create", "speca_sched_destroy", "speca_sched_plan", "speca_sched_commit",
+            "speca_ring_weights", "speca_sched_create", "speca_sched_destroy", "speca_sched_plan", "speca_sched_commit",
             "speca_sched_refs"]
 
 
@@ -141,8 +143,8 @@ def _p(a: np.ndarray, ct):
 
 
 def make_cfg(order=2, interval=5, verify_block=-1, coef_mode=COEF_TAYLOR, eps=1e-8, warmup_full=1,
-             metric=METRIC_L2) -> Cfg:
-    return Cfg(order, interval, verify_block, coef_mode, eps, warmup_full, metric)
+             metric=METRIC_L2, layout=CACHE_DIFFERENCES) -> Cfg:
+    return Cfg(order, interval, verify_block, coef_mode, eps, warmup_full, metric, layout)
 
 
 # ---- host-only helpers ------------------------------------------------------------------
@@ -165,6 +167,15 @@ def coefficients(mode: int, step: int, refs: Sequence[int], order: int) -> np.nd
     out = np.zeros(order + 1, np.float32)
     _check(None, load_library().speca_coefficients(mode, step, _p(r, C.c_int32), len(r), order, _p(out, C.c_float)))
     return out
+
+
+def ring_weights(mode: int, order: int, full_steps: Sequence[int], step: int):
+    """-> (weights by age [n], planes by age [n]) of the ring layout after the given full steps."""
+    r = _i32(full_steps)
+    w = np.zeros(order + 1, np.float32); pl = np.zeros(order + 1, np.int32); n = C.c_int(0)
+    _check(None, load_library().speca_ring_weights(mode, order, _p(r, C.c_int32), len(r), step, _p(w, C.c_float), _p(pl, C.c_int32),
+                                                   C.byref(n)))
+    return w[:n.value], pl[:n.value]
 
 
 def divisors(mode: int, step: int, refs: Sequence[int], order: int) -> np.ndarray:

@@ -41,8 +41,14 @@ Error build_forecast_table(const speca_ctx* ctx, int step, const int32_t* rows, 
     rt->row[i] = rows[i];
     rt->order[i] = order;
     for (int o = 0; o < kMaxTensors; ++o) rt->w[i][o] = 0.0f;
-    if (!forecast_coefficients(ctx->cfg.coef_mode, step, h.r, h.n, order, rt->w[i]))
+    if (ctx->cfg.layout == SPECA_CACHE_RING) {
+      int planes = 0;                                     // weights per plane; every held plane is read
+      if (!ctx->row_ring[rows[i]].forecast(ctx->cfg.coef_mode, step, h, ctx->cfg.order, rt->w[i], &planes))
+        SPECA_FAIL(SPECA_EINVAL, "cannot form forecast weights for row %d", rows[i]);
+      rt->order[i] = planes - 1;
+    } else if (!forecast_coefficients(ctx->cfg.coef_mode, step, h.r, h.n, order, rt->w[i])) {
       SPECA_FAIL(SPECA_EINVAL, "cannot form forecast coefficients for row %d", rows[i]);
+    }
   }
   return ok();
 }
@@ -58,6 +64,11 @@ Error build_refresh_table(const speca_ctx* ctx, int step, const int32_t* rows, i
     rt->order[i] = order;
     float d[kMaxTensors] = {0};
     for (int o = 0; o < kMaxTensors; ++o) rt->w[i][o] = 0.0f;
+    if (ctx->cfg.layout == SPECA_CACHE_RING) {            // one store into the next plane, nothing read
+      rt->row[i] = rows[i] + ctx->row_ring[rows[i]].next_plane(ctx->cfg.order) * ctx->batch_rows;
+      rt->order[i] = 0;
+      continue;
+    }
     if (!refresh_divisors(ctx->cfg.coef_mode, step, h.r, h.n, order, d))
       SPECA_FAIL(SPECA_EINVAL, "cannot form refresh divisors for row %d", rows[i]);
     for (int o = 0; o < order; ++o) rt->w[i][o] = 1.0f / d[o];
@@ -66,7 +77,16 @@ Error build_refresh_table(const speca_ctx* ctx, int step, const int32_t* rows, i
 }
 
 void push_refs(speca_ctx* ctx, int step, const int32_t* rows, int n) {
-  for (int i = 0; i < n; ++i) ctx->row_refs[rows[i]].push(step, ctx->cfg.order);
+  for (int i = 0; i < n; ++i) {
+    if (ctx->cfg.layout == SPECA_CACHE_RING)
+      (void)ctx->row_ring[rows[i]].push(ctx->cfg.coef_mode, step, ctx->row_refs[rows[i]], ctx->cfg.order);   // validated by build_refresh_table
+    ctx->row_refs[rows[i]].push(step, ctx->cfg.order);
+  }
+}
+
+void clear_refs(speca_ctx* ctx) {
+  ctx->row_refs.assign(ctx->batch_rows, RefHistory());
+  ctx->row_ring.assign(ctx->batch_rows, RingWeights());
 }
 
 Error ensure_partial(speca_ctx* ctx, size_t floats) {
@@ -96,6 +116,7 @@ static bool cfg_ok(const speca_cfg* c, std::string* why) {
   if (!(c->eps >= 0.0f)) { *why = "eps < 0"; return false; }
   if (c->metric < SPECA_METRIC_L2 || c->metric > SPECA_METRIC_COSINE) { *why = format("metric = %d", c->metric); return false; }
   if (c->verify_block < -1) { *why = format("verify_block = %d", c->verify_block); return false; }
+  if (c->layout != SPECA_CACHE_DIFFERENCES && c->layout != SPECA_CACHE_RING) { *why = format("layout = %d", c->layout); return false; }
   return true;
 }
 
@@ -233,7 +254,7 @@ static Error init_cache_impl(speca_ctx* ctx, const speca_cfg* cfg, int batch_row
   ctx->geom = g;
   ctx->cfg = *cfg;
   ctx->batch_rows = batch_rows;
-  ctx->row_refs.assign(batch_rows, RefHistory());
+  clear_refs(ctx);
   if (ctx->model) SPECA_TRY(ctx->model->prepare(ctx, batch_rows));
   ctx->cache_ready = true;
   return ok();

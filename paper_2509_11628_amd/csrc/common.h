@@ -41,7 +41,9 @@ inline size_t dtype_size(int dtype) { return dtype == SPECA_BF16 ? 2 : 4; }
 // ---- launch-time tables (passed by value as kernel arguments) ------------------------------
 // Row i of a compact launch works on cache row row[i] with its own available order and
 // its own fp32 weights: forecast coefficients c_i (Eq. 2) or reciprocal divisors of the
-// difference recursion (Eq. 3).
+// difference recursion (Eq. 3).  row[i] indexes the [plane][batch_rows] grid of a slot:
+// row + plane * batch_rows with planes 0..order[i] counted from there.  The plane part is
+// non-zero only for a refresh in the ring layout (order 0: one store into the row's next plane).
 struct RowTable {
   int32_t n;
   int32_t row[kMaxRows];

@@ -41,6 +41,7 @@ struct speca_ctx {
   speca::CacheGeom geom{};
   size_t cache_cap = 0;                       // bytes allocated at geom.base
   std::vector<speca::RefHistory> row_refs;    // per cache row
+  std::vector<speca::RingWeights> row_ring;   // per cache row (ring layout only)
 
   // Lanes: the rows of one launch are independent, so a step can run its row groups side by side
   // on streams of its own (lane 0 is `stream`).  While one group sits in an HBM-bound epilogue or
@@ -95,6 +96,8 @@ Error build_forecast_table(const speca_ctx* ctx, int step, const int32_t* rows, 
 Error build_refresh_table(const speca_ctx* ctx, int step, const int32_t* rows, int n, RowTable* rt);
 // Record `step` as the latest reference of the rows.
 void push_refs(speca_ctx* ctx, int step, const int32_t* rows, int n);
+// Forget every reference (a new trajectory).
+void clear_refs(speca_ctx* ctx);
 Error ensure_partial(speca_ctx* ctx, size_t floats);
 Error check_rows(const speca_ctx* ctx, const int32_t* rows, int n_rows);
 

@@ -33,7 +33,7 @@ Error launch_gemm(int dtype, const void* A, int64_t lda, const void* W, int64_t 
           epi.g.E < epi.cache_elem_offset + static_cast<int64_t>(epi.tokens) * N || epi.slot < 0 || epi.slot >= epi.g.n_slots)
         SPECA_FAIL(SPECA_EINVAL, "gemm: cache refresh geometry does not match the launch");
       for (int i = 0; i < epi.rt.n; ++i)
-        if (epi.rt.row[i] < 0 || epi.rt.row[i] >= epi.g.batch_rows || epi.rt.order[i] > epi.g.m)
+        if (epi.rt.row[i] < 0 || epi.rt.order[i] < 0 || epi.rt.row[i] / epi.g.batch_rows + epi.rt.order[i] > epi.g.m)   // plane + order
           SPECA_FAIL(SPECA_EINVAL, "gemm: cache row table out of range");
     }
   } else if (!epi.out || epi.ldo < N) {

@@ -83,7 +83,7 @@ Error sample_impl(speca_ctx* ctx, float* latents, int batch, const speca_cond* c
   }
 
   // fresh trajectory: forget all references
-  ctx->row_refs.assign(ctx->batch_rows, RefHistory());
+  clear_refs(ctx);
   speca_sched sched;
   sched.batch = B;
   sched.cfg = ctx->cfg;

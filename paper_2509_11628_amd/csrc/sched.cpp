@@ -58,6 +58,39 @@ bool refresh_divisors(int mode, int step, const int32_t* refs, int n_refs, int o
   return true;
 }
 
+bool RingWeights::push(int mode, int step, const RefHistory& before, int m) {
+  if (m < 0 || m > SPECA_MAX_ORDER || (before.n > 0 && step <= before.r[0])) return false;
+  const int order = before.n < m ? before.n : m;        // differences defined after this step
+  float d[SPECA_MAX_ORDER + 1] = {0};
+  if (!refresh_divisors(mode, step, before.r, before.n, order, d)) return false;
+  double nw[SPECA_MAX_ORDER + 1][SPECA_MAX_ORDER + 1] = {};
+  nw[0][0] = 1.0;
+  for (int i = 1; i <= order; ++i)
+    for (int j = 0; j <= i; ++j) {
+      const double shifted_old = j >= 1 ? W[i - 1][j - 1] : 0.0;
+      nw[i][j] = (nw[i - 1][j] - shifted_old) / static_cast<double>(d[i - 1]);
+    }
+  std::memcpy(W, nw, sizeof(W));
+  head = next_plane(m);
+  count = count < m + 1 ? count + 1 : m + 1;
+  return true;
+}
+
+bool RingWeights::forecast(int mode, int step, const RefHistory& h, int m, float* w, int* planes) const {
+  if (!w || !planes || head < 0 || count < 1 || h.n < 1) return false;
+  const int order = (m < h.n - 1 ? m : h.n - 1) < count - 1 ? (m < h.n - 1 ? m : h.n - 1) : count - 1;
+  float c[SPECA_MAX_ORDER + 1] = {0};
+  if (!forecast_coefficients(mode, step, h.r, h.n, order, c)) return false;
+  for (int p = 0; p < count; ++p) w[p] = 0.0f;
+  for (int j = 0; j <= order; ++j) {                      // feature of age j lives `j` planes behind the head
+    double acc = 0.0;
+    for (int i = j; i <= order; ++i) acc += static_cast<double>(c[i]) * W[i][j];
+    w[((head - j) % (m + 1) + (m + 1)) % (m + 1)] = static_cast<float>(acc);
+  }
+  *planes = count;
+  return true;
+}
+
 void tau_geometric(float tau0, float beta, int steps, float* out) {
   for (int s = 0; s < steps; ++s)
     out[s] = static_cast<float>(static_cast<double>(tau0) * std::pow(static_cast<double>(beta), static_cast<double>(s) / steps));
@@ -74,7 +107,8 @@ void tau_linear(float a, float b, int steps, float* out) {
 static bool cfg_valid(const speca_cfg* c) {
   return c && c->order >= 0 && c->order <= SPECA_MAX_ORDER && c->interval >= 1 && c->warmup_full >= 1 &&
          (c->coef_mode == SPECA_COEF_TAYLOR || c->coef_mode == SPECA_COEF_NEWTON || c->coef_mode == SPECA_COEF_ADAMS_BASHFORTH) && c->eps >= 0.0f &&
-         c->metric >= SPECA_METRIC_L2 && c->metric <= SPECA_METRIC_COSINE && c->verify_block >= -1;
+         c->metric >= SPECA_METRIC_L2 && c->metric <= SPECA_METRIC_COSINE && c->verify_block >= -1 &&
+         (c->layout == SPECA_CACHE_DIFFERENCES || c->layout == SPECA_CACHE_RING);
 }
 
 extern "C" {
@@ -98,6 +132,27 @@ int speca_coefficients(int coef_mode, int step, const int32_t* refs, int n_refs,
 int speca_divisors(int coef_mode, int step, const int32_t* refs, int n_refs, int order, float* d_out) {
   if (order < 0 || (order > 0 && !d_out)) return SPECA_EINVAL;
   return speca::refresh_divisors(coef_mode, step, refs, n_refs, order, d_out) ? SPECA_OK : SPECA_EINVAL;
+}
+
+int speca_ring_weights(int coef_mode, int order, const int32_t* full_steps, int n_full, int step, float* w_out, int32_t* plane_out,
+                       int* n_out) {
+  if (!full_steps || n_full < 1 || !w_out || !plane_out || !n_out || order < 0 || order > SPECA_MAX_ORDER) return SPECA_EINVAL;
+  speca::RefHistory h;
+  speca::RingWeights ring;
+  for (int i = 0; i < n_full; ++i) {
+    if (!ring.push(coef_mode, full_steps[i], h, order)) return SPECA_EINVAL;
+    h.push(full_steps[i], order);
+  }
+  float w[SPECA_MAX_ORDER + 1];
+  int planes = 0;
+  if (!ring.forecast(coef_mode, step, h, order, w, &planes)) return SPECA_EINVAL;
+  for (int j = 0; j < planes; ++j) {                       // report by age: 0 = latest feature
+    const int p = ((ring.head - j) % (order + 1) + (order + 1)) % (order + 1);
+    w_out[j] = w[p];
+    plane_out[j] = p;
+  }
+  *n_out = planes;
+  return SPECA_OK;
 }
 
 int speca_sched_create(speca_sched** out, int batch, const speca_cfg* cfg) {

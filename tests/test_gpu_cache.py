@@ -93,6 +93,47 @@ def test_refresh_forecast_parity(slots, B, T, D, dtype, mode):
     ctx.close()
 
 
+@pytest.mark.parametrize("slots,B,T,D,dtype", [CASES[0], CASES[1], CASES[3], CASES[4]])
+@pytest.mark.parametrize("mode", ["taylor", "newton", "adams_bashforth"])
+@pytest.mark.parametrize("m", [0, 2, 3])
+def test_ring_layout_refresh_forecast_parity(slots, B, T, D, dtype, mode, m):
+    """Raw-feature ring layout: per-row histories that differ, more full steps than planes (the
+    ring wraps), forecasts during the warm-up; against the oracle's ring cache, which forms the
+    differences from the stored features by the recursion's definition."""
+    sp = _sp()
+    from paper_2509_11628_amd import binding as bd
+    dt = bd.BF16 if dtype == "bf16" else bd.F32
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    code = {"taylor": bd.COEF_TAYLOR, "newton": bd.COEF_NEWTON, "adams_bashforth": bd.COEF_ADAMS_BASHFORTH}[mode]
+    ctx = sp.Context(sp.cache_only_desc(slots, T, D, dt))
+    ctx.init_cache(sp.make_cfg(order=m, interval=100, coef_mode=code, layout=bd.CACHE_RING), B)
+    oc = [core.make_cache("ring", slots, m, mode, dtype) for _ in range(B)]
+    plan = [(0, list(range(B))), (3, list(range(B))), (4, [r for r in range(B) if r % 2 == 0]), (9, list(range(B))),
+            (11, [r for r in range(B) if r % 2 == 1]), (12, list(range(B))), (17, list(range(B)))]
+    feats = si.feature_trajectory(slots, B, T, D, [p[0] for p in plan], seed=9, dtype=dtype)
+    for n, ((s, rows), f) in enumerate(zip(plan, feats)):
+        sub = np.ascontiguousarray(f[:, rows])
+        ctx.refresh(s, rows, _dev(sub, dtype))
+        for i, r in enumerate(rows):
+            oc[r].refresh(s, [sub[j, i] for j in range(slots)])
+        for step in (s + 1, s + 3):
+            rows_f = list(range(B))
+            out = torch.empty((slots, B, T, D), dtype=td, device="cuda")
+            ctx.forecast(step, rows_f, out)
+            got = _host(out)
+            exp = np.stack([np.stack([oc[r].forecast(step, j) for r in rows_f]) for j in range(slots)])
+            if dtype == "f32":
+                assert max_abs_rel(got, exp) <= 1e-5, (n, step)
+            else:
+                expb = core.bf16_round(exp)
+                # fp32 sum of up to m+1 terms that partly cancel: allow the rounding boundary to move by the
+                # fp32 noise of the largest term as well
+                ulp = np.abs(expb) * 2.0 ** -7 + 1e-5
+                assert np.all(np.abs(got - expb) <= ulp), (n, step)
+                assert np.mean(got != expb) < 0.03, (n, step)
+    ctx.close()
+
+
 def test_bf16_cache_vs_unrounded_oracle():
     sp = _sp()
     from paper_2509_11628_amd import binding as bd

@@ -114,8 +114,9 @@ def _run_both(s, om, ctx, S, B, cfg_kwargs, tau, cfg_scale=0.0, seed=0, solver="
     sol = osamp.Solver(solver, ts, ab, cfg_scale, noise)
     exp, tr = osamp.sample(om, osamp.SpecaConfig(cache_store="bf16" if s.dtype == "bf16" else None, **cfg_kwargs), sol, tau, lat, lab)
     mode = {"newton": bd.COEF_NEWTON, "adams_bashforth": bd.COEF_ADAMS_BASHFORTH}.get(cfg_kwargs.get("mode"), bd.COEF_TAYLOR)
-    kw = {k: v for k, v in cfg_kwargs.items() if k != "mode"}
-    ctx.init_cache(sp.make_cfg(coef_mode=mode, **kw), B * (2 if cfg_scale > 0 else 1))
+    kw = {k: v for k, v in cfg_kwargs.items() if k not in ("mode", "cache_layout")}
+    layout = bd.CACHE_RING if cfg_kwargs.get("cache_layout") == "ring" else bd.CACHE_DIFFERENCES
+    ctx.init_cache(sp.make_cfg(coef_mode=mode, layout=layout, **kw), B * (2 if cfg_scale > 0 else 1))
     xd = torch.from_numpy(lat).cuda()
     got = ctx.sample(xd, ts, ab, tau, cfg_scale=cfg_scale, labels=lab,
                      solver_kind=bd.SOLVER_DDPM if solver == "ddpm" else bd.SOLVER_DDIM,
@@ -230,6 +231,29 @@ def test_guided_trajectory(tiny):
         m = ~np.isnan(tr.err)
         assert np.array_equal(~np.isnan(gtr["err"]), m)
         np.testing.assert_allclose(gtr["err"][m], tr.err[m], rtol=1e-3 if s.dtype == "f32" else 1.5e-1, atol=0 if s.dtype == "f32" else 5e-3)
+
+
+def test_ring_layout_trajectories(tiny):
+    """The raw-feature ring layout of the cache through whole trajectories (fused refresh in the
+    branch epilogues, forecast-and-fold, verification), against the oracle's ring cache."""
+    s, w, om, ctx = tiny
+    tau = core.tau_linear(0.05, 0.01, 20)
+    for kw, scale in ((dict(order=1, interval=4), 0.0), (dict(order=2, interval=5, mode="newton"), 0.0),
+                      (dict(order=3, interval=6, mode="adams_bashforth"), 0.0), (dict(order=2, interval=4), 1.5)):
+        kw = dict(kw, cache_layout="ring")
+        exp, tr, got, gtr = _run_both(s, om, ctx, 20, 2, kw, tau, cfg_scale=scale, seed=5)
+        compared, complete = compare_traces(tr, gtr, s.dtype)
+        print(f"\n[{s.dtype}] ring {kw}: kinds {tr.kind.tolist()} compared {compared} complete {complete}")
+        assert compared >= 4, kw
+        if s.dtype == "f32":
+            assert complete, kw
+        if complete:
+            assert max_abs_rel(got, exp) <= _tol(s), kw
+    # tau = 0: plain sampling, and the layout cannot matter (no forecast is ever used)
+    z = np.zeros(20, np.float32)
+    _, _, got_ring, g1 = _run_both(s, om, ctx, 20, 2, dict(order=2, interval=4, cache_layout="ring"), z)
+    _, _, got_diff, g2 = _run_both(s, om, ctx, 20, 2, dict(order=2, interval=4), z)
+    assert got_ring.tobytes() == got_diff.tobytes() and np.all(g1["kind"] == 0)
 
 
 def test_stochastic_solver_trajectory(tiny):
@@ -359,14 +383,20 @@ def test_config3_full_size_sampled():
     S = 4
     ts, ab = si.ddim_tables(S)
     tau = np.array([0.0, np.inf, 1e-3, np.inf], np.float32)
-    ctx.set_lanes(4)
-    ctx.init_cache(sp.make_cfg(order=2, interval=5), 2 * B)
-    x = torch.from_numpy(lat).cuda()
-    gtr = ctx.sample(x, ts, ab, tau, cfg_scale=1.5, labels=lab)
     sol = osamp.Solver("ddim", ts, ab, 1.5)
-    exp1, tr = osamp.sample(om, osamp.SpecaConfig(order=2, interval=5, cache_store="bf16"), sol, tau, lat[:1], lab[:1])
-    assert tr.kind[0].tolist() == [0, 1, 2, 1] and gtr["kind"][0].tolist() == [0, 1, 2, 1]
-    compared, complete = compare_traces(tr, {"kind": gtr["kind"][:1], "err": gtr["err"][:1]}, "bf16")
-    assert compared == 3 and complete
-    assert max_abs_rel(x[:1].cpu().numpy(), exp1) <= 2e-2
+    for layout, code in (("differences", bd.CACHE_DIFFERENCES), ("ring", bd.CACHE_RING)):      # both layouts of the cache
+        finals = []
+        for lanes in (4, 1):
+            ctx.set_lanes(lanes)
+            ctx.init_cache(sp.make_cfg(order=2, interval=5, layout=code), 2 * B)
+            x = torch.from_numpy(lat).cuda()
+            gtr = ctx.sample(x, ts, ab, tau, cfg_scale=1.5, labels=lab)
+            finals.append(x.cpu().numpy())
+        assert np.array_equal(finals[0], finals[1]), layout
+        exp1, tr = osamp.sample(om, osamp.SpecaConfig(order=2, interval=5, cache_store="bf16", cache_layout=layout), sol, tau,
+                                lat[:1], lab[:1])
+        assert tr.kind[0].tolist() == [0, 1, 2, 1] and gtr["kind"][0].tolist() == [0, 1, 2, 1], layout
+        compared, complete = compare_traces(tr, {"kind": gtr["kind"][:1], "err": gtr["err"][:1]}, "bf16")
+        assert compared == 3 and complete, layout
+        assert max_abs_rel(finals[0][:1], exp1) <= 2e-2, layout
     ctx.close()

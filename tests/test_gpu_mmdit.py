@@ -72,8 +72,9 @@ def _run_both(s, om, ctx, S, B, cfg_kwargs, tau, seed=0):
     conds = [(txt[b], vec[b]) for b in range(B)]
     exp, tr = osamp.sample(om, osamp.SpecaConfig(cache_store="bf16" if s.dtype == "bf16" else None, **cfg_kwargs), sol, tau, x, conds)
     mode = bd.COEF_NEWTON if cfg_kwargs.get("mode") == "newton" else bd.COEF_TAYLOR
-    kw = {k: v for k, v in cfg_kwargs.items() if k != "mode"}
-    ctx.init_cache(sp.make_cfg(coef_mode=mode, **kw), B)
+    kw = {k: v for k, v in cfg_kwargs.items() if k not in ("mode", "cache_layout")}
+    layout = bd.CACHE_RING if cfg_kwargs.get("cache_layout") == "ring" else bd.CACHE_DIFFERENCES
+    ctx.init_cache(sp.make_cfg(coef_mode=mode, layout=layout, **kw), B)
     xd = torch.from_numpy(x).cuda()
     td, vd = torch.from_numpy(txt).cuda().to(_td(s)), torch.from_numpy(vec).cuda().to(_td(s))
     got = ctx.sample(xd, ts, sg, tau, solver_kind=bd.SOLVER_FLOW, txt=td, pooled=vd)
@@ -85,7 +86,8 @@ def test_flow_trajectory_mixed_schedule(tiny):
     S = 12
     tau = core.tau_linear(0.02, 0.004, S)
     for kw in (dict(order=1, interval=4), dict(order=2, interval=4, mode="newton"), dict(order=2, interval=5, verify_block=0),
-               dict(order=2, interval=5, verify_block=s.depth_dual)):
+               dict(order=2, interval=5, verify_block=s.depth_dual),
+               dict(order=2, interval=4, cache_layout="ring"), dict(order=3, interval=5, mode="newton", cache_layout="ring")):
         exp, tr, got, gtr = _run_both(s, om, ctx, S, 2, kw, tau)
         compared, complete = compare_traces(tr, gtr, s.dtype)
         print(f"\n[{s.dtype}] {kw}: kinds {tr.kind.tolist()} compared {compared} complete {complete}")

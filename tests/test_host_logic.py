@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol(bd):
 def test_struct_layouts_match_header(bd):
     import ctypes as C
     assert C.sizeof(bd.ModelDesc) == 19 * 4
-    assert C.sizeof(bd.Cfg) == 7 * 4
+    assert C.sizeof(bd.Cfg) == 8 * 4
     assert C.sizeof(bd.Profile) == 6 * 8 * 4
     assert bd.MAX_ORDER == 4 and bd.MAX_LAUNCH_ROWS == 64
 
@@ -58,6 +58,34 @@ def test_coefficients_and_divisors_match_oracle(bd, mode):
         bd.coefficients(code, 5, [3], 1)           # order needs two references
     with pytest.raises(bd.SpecaError):
         bd.coefficients(7, 5, [3], 0)              # unknown policy
+
+
+@pytest.mark.parametrize("mode", ["taylor", "newton", "adams_bashforth"])
+def test_ring_weights_reproduce_the_oracle_forecast(bd, mode):
+    """Ring layout: the library's per-feature weights, applied to the raw features, give the
+    oracle's forecast (difference layout and ring layout, nothing rounded) for irregular
+    histories of every length, and the planes rotate."""
+    code = {"taylor": bd.COEF_TAYLOR, "newton": bd.COEF_NEWTON, "adams_bashforth": bd.COEF_ADAMS_BASHFORTH}[mode]
+    rng = np.random.default_rng(5)
+    for m in range(0, 5):
+        steps = np.cumsum(rng.integers(1, 6, size=9)).tolist()
+        feats = [rng.standard_normal(6) for _ in steps]
+        diff = core.FeatureCache(1, m, mode); ring = core.make_cache("ring", 1, m, mode)
+        for n, (s, f) in enumerate(zip(steps, feats), start=1):
+            diff.refresh(s, [f]); ring.refresh(s, [f])
+            for k in (1, 3):
+                w, planes = bd.ring_weights(code, m, steps[:n], s + k)
+                assert len(w) == min(m + 1, n)
+                assert planes.tolist() == [(n - 1 - j) % (m + 1) for j in range(len(w))]      # age j sits j planes behind
+                got = sum(float(w[j]) * feats[n - 1 - j] for j in range(len(w)))
+                scale = sum(abs(float(w[j])) for j in range(len(w)))
+                np.testing.assert_allclose(got, diff.forecast(s + k, 0), rtol=0, atol=3e-7 * scale * 4)
+                np.testing.assert_allclose(got, ring.forecast(s + k, 0), rtol=0, atol=3e-7 * scale * 4)
+                assert abs(float(np.sum(w)) - 1.0) < 1e-5 * scale       # constants are forecast exactly
+    with pytest.raises(bd.SpecaError):
+        bd.ring_weights(code, 2, [3, 3], 5)             # full steps must increase
+    with pytest.raises(bd.SpecaError):
+        bd.ring_weights(code, 2, [1, 3], 3)             # forecast step not after the latest full step
 
 
 def test_threshold_helpers_match_oracle(bd):
