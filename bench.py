@@ -38,7 +38,7 @@ PEAK_HBM_GBPS = 8000.0         # MI355X HBM3E
 # same counters; launch-weighted over the kernels of the class).  Counters cannot be read from
 # inside the process, so the figures are carried here; profiles/hbm_counters.txt holds the runs.
 MEASURED_TRAFFIC = {
-    ("dit_xl2", "gemm"): 134.1e6,
+    ("dit_xl2", "gemm"): 119.8e6,
     ("forecast", "forecast"): 528.5e6,
 }
 
@@ -190,6 +190,7 @@ def bench_mmdit(args, which):
     from paper_2509_11628_amd import binding as bd
     shape = si.mmdit_flux() if which == "flux" else si.mmdit_hunyuan()
     w = device_mmdit_weights(shape)
+    print(f"bench.py: {which} weights on the device", file=sys.stderr, flush=True)
     ctx = sp.Context(sp.mmdit_desc(shape), w)
     order = 2
     ctx.init_cache(sp.make_cfg(order=order, interval=args.interval, layout=_layout(args)), 1)
@@ -209,6 +210,7 @@ def bench_mmdit(args, which):
         dt = time.perf_counter() - t0
         prof = ctx.profile_end() if profile else None
         assert bool(torch.isfinite(x).all()), "non-finite latents"
+        print(f"bench.py: {which} trajectory of {steps} steps done in {dt:.1f} s", file=sys.stderr, flush=True)
         return dt, tr, prof, x
 
     K = args.steps
