@@ -15,9 +15,15 @@
 // half-wave h), and V^T is read from LDS in that same order.
 // V is transposed on its way into LDS (register transposes of 4-key x 8-dim blocks) into a swizzled,
 // key-permuted layout.
-// Two kernels: a tiled one (keys/values in 64-key tiles, online softmax) and, for T <= 256, one that
-// holds the whole sequence of a head in LDS and takes the softmax in one pass.
+// Three kernels: a tiled one (keys/values in 64-key tiles staged through registers, online softmax); for
+// head_dim 128 a tiled one whose tiles go global -> LDS directly and whose V^T fragments come from the
+// transposing LDS read (no staging, no register transposes; the next tile's scores are issued under the
+// current tile's softmax); and, for T <= 256, one that holds the whole sequence of a head in LDS and takes
+// the softmax in one pass.
 // head_dim is padded with zeros to a multiple of 16 for q k^T and of 32 for P V.
+#include <cstdlib>
+#include <type_traits>
+
 #include "gemm.h"
 
 namespace speca {
@@ -278,6 +284,257 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(const uint16_t* 
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Tiled kernel for head_dim 128 whose key and value tiles go global -> LDS directly
+// (global_load_lds_dwordx4: lane l's 16 bytes land at the wave-uniform LDS address + 16 l) and whose
+// V^T operand is formed by the transposing LDS read, so nothing is staged or transposed in registers.
+//
+// Both tiles are stored row-major as they are in memory: 64 keys x 256 bytes (16 chunks of 16 bytes).
+// One load instruction covers 4 rows; lane l supplies the chunk stored at position l % 16 of row l / 16.
+// Keys:   S^T = K q^T reads, per lane, chunk 2 ks + h of row l32 (ds_read_b128); chunk c of row r sits at
+//         position c ^ (r & 15), so the 16 lanes of a read phase touch all 64 banks once.
+// Values: ds_read_b64_tr_b16, per group of 16 lanes: lane j points at 4 consecutive dims
+//         d0 + 4 (j % 4) of key k0 + j / 4, and lane i of the group receives dim d0 + i of the keys
+//         k0 .. k0 + 3 (measured lane layout).  Two such reads (keys 16 t + 4 h + 0..3 and
+//         16 t + 8 + 4 h + 0..3) are one A fragment of V^T in exactly the key order the S^T
+//         accumulators hand P^T to the second MFMA.  The four rows a half-wave reads are moved to
+//         different 64-byte bank groups: chunk c of row r sits at position
+//         c ^ (4 (r & 3) + ((r >> 2) & 3)).
+// Rows beyond T are read from row T - 1 (valid memory): their scores are masked to -inf, so their
+// probabilities are exactly 0 and the finite values they multiply do not matter.
+// Ring: two buffers; per tile the waves wait for their own loads with vmcnt(0) (the only safe wait
+// for these loads), one barrier, loads of the next tile are issued into the buffer just freed.
+#define SPECA_ATTN_GLL(src, dst)                                                                                  \
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),                         \
+                                   (__attribute__((address_space(3))) void*)(dst), 16, 0, 0)
+typedef short short4v __attribute__((ext_vector_type(4)));
+
+template <bool PIPE>
+__global__ __launch_bounds__(256, 2) void attention_dma_kernel(const uint16_t* __restrict__ qkv, uint16_t* __restrict__ out, int64_t ldo,
+                                                            int T, int H, float scale_log2e) {
+  constexpr int HD = 128, KS = 8, DT = 4;
+  constexpr int TILE = 64 * HD;               // elements of one key or value tile
+  extern __shared__ __align__(16) uint16_t smem[];
+  uint16_t* Ks = smem;                        // [2][64][128]
+  uint16_t* Vs = smem + 2 * TILE;             // [2][64][128]
+
+  const int row = blockIdx.z, head = blockIdx.y, q0 = blockIdx.x * 128;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int64_t D = static_cast<int64_t>(H) * HD;
+  const uint16_t* base = qkv + static_cast<int64_t>(row) * T * 3 * D + head * HD;
+
+  Frag qf[KS];
+  {
+    const int q = q0 + wave * 32 + l32;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      qf[ks].u = q < T ? *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(q) * 3 * D + ks * 16 + lhi * 8) : make_uint4(0, 0, 0, 0);
+  }
+  floatx16 o[DT];
+#pragma unroll
+  for (int i = 0; i < DT; ++i)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) o[i][q] = 0.0f;
+  float mrun = -INFINITY, lrun = 0.0f;
+
+  // loader: wave w issues instructions i = w, w + 4, w + 8, w + 12 of each tile (16 per tile, 4 rows each);
+  // lane -> row 4 i + lane / 16, stored position lane % 16
+  const int lr = lane >> 4, lp = lane & 15;
+  // The source chunk of a lane does not depend on the instruction (rows 4 i + lr with i = wave + 4 g: r & 15 and
+  // the value swizzle only see 4 wave + lr), so a tile's addresses are one per-lane 32-bit offset on top of a
+  // wave-uniform row pointer: no per-load vector arithmetic.  Only a ragged last tile clamps rows per lane.
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int row3d = static_cast<int>(3 * D);
+  const int koff = lr * row3d + static_cast<int>(D) + ((lp ^ ((4 * wave_u + lr) & 15)) << 3);
+  const int voff = lr * row3d + 2 * static_cast<int>(D) + ((lp ^ (4 * lr + (wave_u & 3))) << 3);
+  auto issue = [&](int k0, int buf, uint16_t* dst, int off) {
+    if (k0 + 64 <= T) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int i = wave_u + 4 * g;
+        const uint16_t* ub = base + static_cast<int64_t>(k0 + 4 * i) * row3d;      // wave-uniform
+        SPECA_ATTN_GLL(ub + off, dst + buf * TILE + i * 512);
+      }
+    } else {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int i = wave_u + 4 * g;
+        int key = k0 + 4 * i + lr;
+        key = key < T ? key : T - 1;
+        SPECA_ATTN_GLL(base + static_cast<int64_t>(key) * row3d + (off - lr * row3d), dst + buf * TILE + i * 512);
+      }
+    }
+  };
+  auto issue_k = [&](int k0, int buf) { issue(k0, buf, Ks, koff); };
+  auto issue_v = [&](int k0, int buf) { issue(k0, buf, Vs, voff); };
+  const int kpos_sw = l32 & 15;               // key row l32 (+32): r & 15
+  // value reader: 16-lane group g = lane / 16, j = lane % 16: key k0 + j / 4 with k0 = 16 t + 4 (g >> 1) (+ 8),
+  // dims dt * 32 + 16 (g & 1) + 4 (j % 4) .. + 3: chunk dt * 4 + 2 (g & 1) + (j % 4) / 2, half (j % 2)
+  const int vg = lane >> 4, vj = lane & 15;
+  const int vkey0 = 4 * (vg >> 1) + (vj >> 2);                     // key inside the 16-key step, first read (second: + 8)
+  const int vchunk0 = 2 * (vg & 1) + ((vj & 3) >> 1);              // chunk inside the 32-dim block
+  const int vhalf = (vj & 1) * 4;                                  // element offset inside the chunk
+
+  // S^T of the 64 keys in key buffer kb
+  auto scores = [&](floatx16 (&s)[2], int kb) {
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) s[st][q] = 0.0f;
+      const uint16_t* kp = Ks + kb * TILE + (st * 32 + l32) * HD;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        Frag kf;
+        kf.u = *reinterpret_cast<const uint4*>(kp + (((2 * ks + lhi) ^ kpos_sw) << 3));
+        s[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, s[st], 0, 0, 0);
+      }
+    }
+  };
+  // online softmax of tile kt (scores in s, replaced by probabilities), then O^T += V^T P^T from value buffer vb
+  auto softmax_pv = [&](floatx16 (&s)[2], int kt, int vb, auto masked) {
+    const int kbase = kt * 64;
+    if (decltype(masked)::value && kbase + 64 > T) {
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          const int key = kbase + st * 32 + 8 * (q >> 2) + 4 * lhi + (q & 3);
+          if (key >= T) s[st][q] = -INFINITY;
+        }
+    }
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) tmax = fmaxf(tmax, s[st][q]);
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float mnew = fmaxf(mrun, tmax);
+    const float moff = mnew * scale_log2e;
+    float psum = 0.0f;
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const float p = fast_exp2(fmaf(s[st][q], scale_log2e, -moff));
+        s[st][q] = p;
+        psum += p;
+      }
+    if (PIPE && !decltype(masked)::value) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // one key fragment read
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA of the next tile's scores
+        __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);     // two exponentials of this tile's softmax
+        __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);     // seven of its other vector instructions
+      }
+    }
+    if (__any(mnew != mrun)) {
+      const float corr = fast_exp2(mrun * scale_log2e - moff);
+      lrun *= corr;
+#pragma unroll
+      for (int i = 0; i < DT; ++i)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) o[i][q] *= corr;
+      mrun = mnew;
+    }
+    lrun += psum;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int st = t >> 1, j0 = (t & 1) * 8;
+      Frag pf;
+      pf.u = make_uint4(cvt_pk_bf16(s[st][j0], s[st][j0 + 1]), cvt_pk_bf16(s[st][j0 + 2], s[st][j0 + 3]),
+                        cvt_pk_bf16(s[st][j0 + 4], s[st][j0 + 5]), cvt_pk_bf16(s[st][j0 + 6], s[st][j0 + 7]));
+      const int ka = 16 * t + vkey0, kb = ka + 8;                  // rows of the two transposing reads
+      const int swa = 4 * (ka & 3) + ((ka >> 2) & 3), swb = 4 * (kb & 3) + ((kb >> 2) & 3);
+      const uint16_t* va = Vs + vb * TILE + ka * HD + vhalf;
+      const uint16_t* vbp = Vs + vb * TILE + kb * HD + vhalf;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        const int c = dt * 4 + vchunk0;
+        const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(va + ((c ^ swa) << 3)));
+        const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(vbp + ((c ^ swb) << 3)));
+        union { short4v h[2]; bf16x8 v; } vf;
+        vf.h[0] = lo; vf.h[1] = hi;
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[dt], 0, 0, 0);
+      }
+    }
+  };
+
+  const int ntiles = (T + 63) / 64;
+  if (!PIPE) {
+    issue_k(0, 0);
+    issue_v(0, 0);
+    for (int kt = 0; kt < ntiles; ++kt) {
+      const int buf = kt & 1;
+      __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): this wave's loads of tile kt (nothing else is outstanding)
+      __syncthreads();                           // tile kt is in LDS; everyone is done with the other buffer
+      if (kt + 1 < ntiles) { issue_k((kt + 1) * 64, buf ^ 1); issue_v((kt + 1) * 64, buf ^ 1); }
+      floatx16 s[2];
+      scores(s, buf);
+      softmax_pv(s, kt, buf, std::true_type());
+    }
+  } else {
+    // The scores of tile kt + 1 are issued before the softmax of tile kt: their MFMAs run while the vector
+    // unit takes exponentials.  Keys are therefore fetched two tiles ahead, values one: at the top of
+    // iteration kt the wave's outstanding loads are K(kt + 1) and V(kt), both awaited with vmcnt(0);
+    // K(kt + 2) then overwrites K(kt) (consumed in iteration kt - 1), V(kt + 1) overwrites V(kt - 1).
+    floatx16 sa[2], sb[2];
+    issue_k(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    if (1 < ntiles) issue_k(64, 1);
+    issue_v(0, 0);
+    scores(sa, 0);
+    // All tiles but the last: no tail mask and no condition between the score MFMAs of tile kt + 1 and the
+    // softmax of tile kt, so both sit in one scheduling region; the group barriers ask for one key-fragment
+    // read and one MFMA per two exponentials and seven other vector instructions (the wave issues in order:
+    // without the interleave the sixteen dependent MFMAs would all be issued before the first exponential).
+#define SPECA_ATTN_ITER(kt_, SC, SN)                                                                              \
+  {                                                                                                               \
+    __builtin_amdgcn_s_waitcnt(0x0F70);                                                                           \
+    __syncthreads();                                                                                              \
+    if ((kt_) + 2 < ntiles) issue_k(((kt_) + 2) * 64, (kt_) & 1);                                                 \
+    issue_v(((kt_) + 1) * 64, ((kt_) + 1) & 1);                                                                   \
+    scores(SN, ((kt_) + 1) & 1);                                                                                  \
+    softmax_pv(SC, (kt_), (kt_) & 1, std::false_type());                                                          \
+  }
+    int kt = 0;
+    for (; kt + 2 < ntiles; kt += 2) {
+      SPECA_ATTN_ITER(kt, sa, sb);
+      SPECA_ATTN_ITER(kt + 1, sb, sa);
+    }
+    if (kt + 1 < ntiles) {                     // two tiles left: kt (scores in sa) and the last one
+      SPECA_ATTN_ITER(kt, sa, sb);
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();
+      softmax_pv(sb, kt + 1, (kt + 1) & 1, std::true_type());
+    } else {                                   // one tile left, its scores are in sa
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();
+      softmax_pv(sa, kt, kt & 1, std::true_type());
+    }
+#undef SPECA_ATTN_ITER
+  }
+
+  const float ltot = lrun + __shfl_xor(lrun, 32, 64);
+  const float inv = 1.0f / ltot;
+  const int q = q0 + wave * 32 + l32;
+  if (q < T) {
+    uint16_t* op = out + (static_cast<int64_t>(row) * T + q) * ldo + head * HD;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int d = dt * 32 + 8 * jj + 4 * lhi;
+        uint2 r;
+        r.x = cvt_pk_bf16(o[dt][4 * jj] * inv, o[dt][4 * jj + 1] * inv);
+        r.y = cvt_pk_bf16(o[dt][4 * jj + 2] * inv, o[dt][4 * jj + 3] * inv);
+        *reinterpret_cast<uint2*>(op + d) = r;
+      }
+  }
+}
+
 // Whole-sequence form for T <= 256: one block of 8 waves per (row, head).  Every key and value of the
 // head is brought into LDS by one wave of loads issued all at once (a single memory round trip, one
 // barrier), each wave then owns 32 queries, holds its complete score row in registers (8 sub-tiles),
@@ -457,6 +714,18 @@ Error launch_hd(const void* qkv, void* out, int64_t ldo, int rows, int T, int H,
     }
     const float sl2 = 1.4426950408889634f / sqrtf(static_cast<float>(HD));
     attention_mfma_whole_kernel<HD><<<dim3(1, H, rows), 512, smem_w, st>>>(static_cast<const uint16_t*>(qkv), static_cast<uint16_t*>(out), ldo, T, H, sl2);
+    SPECA_HIP(hipGetLastError());
+    return ok();
+  }
+  // head_dim 128: direct-to-LDS tiles with the transposing read (SPECA_ATTN=staged keeps the register-staged kernel: A/B timing)
+  // SPECA_ATTN=staged | dma (direct-to-LDS, no overlap of scores and softmax) | pipe (default): A/B timing
+  static const int attn_mode = [] { const char* e = getenv("SPECA_ATTN"); return !e ? 2 : e[0] == 's' ? 0 : e[0] == 'd' ? 1 : 2; }();
+  if (HD == 128 && attn_mode != 0) {
+    constexpr size_t smem_d = static_cast<size_t>(4) * 64 * 128 * sizeof(uint16_t);
+    dim3 grid_d((T + 127) / 128, H, rows);
+    const float sl2 = 1.4426950408889634f / sqrtf(128.0f);
+    if (attn_mode == 1) attention_dma_kernel<false><<<grid_d, 256, smem_d, st>>>(static_cast<const uint16_t*>(qkv), static_cast<uint16_t*>(out), ldo, T, H, sl2);
+    else attention_dma_kernel<true><<<grid_d, 256, smem_d, st>>>(static_cast<const uint16_t*>(qkv), static_cast<uint16_t*>(out), ldo, T, H, sl2);
     SPECA_HIP(hipGetLastError());
     return ok();
   }

@@ -84,7 +84,8 @@ def test_linear_row_result_independent_of_m():
 
 @pytest.mark.parametrize("rows,T,H,hd", [(2, 16, 4, 16), (1, 100, 2, 72), (2, 256, 3, 72), (1, 77, 2, 64), (1, 300, 2, 128), (1, 64, 1, 32),
                                           (1, 256, 2, 128), (3, 200, 2, 64), (1, 257, 2, 72), (1, 33, 1, 128),
-                                          (1, 2000, 2, 128), (1, 1111, 1, 72)])      # many key tiles, ragged tail
+                                          (1, 2000, 2, 128), (1, 1111, 1, 72),       # many key tiles, ragged tail
+                                          (2, 641, 3, 128), (1, 320, 1, 128)])       # several rows and heads; whole tiles only
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_attention(rows, T, H, hd, dtype):
     bd = _bd()
