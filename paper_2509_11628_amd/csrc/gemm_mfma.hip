@@ -429,6 +429,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t
     SPECA_LDFRAG(fa1, fw1, 3);                                                                                    \
     SPECA_MFMAS(fa0, fw0);                                                                                        \
     SPECA_MFMAS(fa1, fw1);                                                                                        \
+    /* keep that order in the instruction stream: two slices of fragments in flight ahead of the MFMAs */         \
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * (TM + TN), 0);                                                \
+    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);                                                      \
+    __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);                                                      \
+    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);                                                      \
+    __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);                                                      \
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * TM * TN, 0);                                                  \
   }
   constexpr int WAIT_VM0 = 0x0F70;                           // s_waitcnt vmcnt(0), other counters untouched
   // prologue: steps 0 .. NS-2, each by its loader waves
