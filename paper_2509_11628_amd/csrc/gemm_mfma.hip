@@ -32,6 +32,9 @@
 #ifndef SPECA_EBU
 #define SPECA_EBU EB
 #endif
+#ifndef SPECA_SPREAD_LOADS
+#define SPECA_SPREAD_LOADS 1
+#endif
 
 namespace speca {
 
@@ -437,6 +440,55 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t
     __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);                                                      \
     __builtin_amdgcn_sched_group_barrier(0x008, 2 * TM * TN, 0);                                                  \
   }
+  // The same compute with the loads of a later K-step spread between its MFMAs.  Issued in a burst right
+  // after the barrier, the loads (a few address instructions each) hold every wave's in-order issue while the
+  // matrix cores idle; here loads and MFMAs sit in one scheduling region (no branch: past the last K-step the
+  // last tile is re-read into the free stage, never consumed, awaited before the epilogue) and the group
+  // barriers ask for the loads one at a time between MFMAs.
+  constexpr int LPW = AG + WG;                               // loads per loader wave and step
+  // Only with the 3-stage ring: there a load has two K-steps to land; with two stages (one step of lead) issuing
+  // the loads later in the step cost more at the next wait than the burst did (measured -3..-5 %).
+  constexpr bool SPREAD = NS == 3 && LPW % 4 == 0 && ((TM * TN) % (LPW / 4) == 0 || LPW / 4 == 3) && SPECA_SPREAD_LOADS;
+#define SPECA_SLICE_GROUPS                                                                                        \
+  {                                                                                                               \
+    constexpr int LPS_ = LPW / 4, MM_ = TM * TN;                                                                  \
+    if (MM_ % LPS_ == 0) {                                                                                        \
+      _Pragma("unroll") for (int l = 0; l < LPS_; ++l) {                                                          \
+        __builtin_amdgcn_sched_group_barrier(0x008, MM_ / LPS_, 0);                                               \
+        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);                                                        \
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                                        \
+      }                                                                                                           \
+    } else { /* 4 MFMAs, 3 loads */                                                                               \
+      _Pragma("unroll") for (int l = 0; l < 3; ++l) {                                                             \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                        \
+        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);                                                        \
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                                        \
+      }                                                                                                           \
+      __builtin_amdgcn_sched_group_barrier(0x008, MM_ - 3, 0);                                                    \
+    }                                                                                                             \
+  }
+#define SPECA_COMPUTE_L(st, new_, ktl_)                                                                           \
+  {                                                                                                               \
+    const uint16_t* as = smem + (st) * STAGE + (wm * WM + l32) * BK;                                              \
+    const uint16_t* ws = smem + (st) * STAGE + BM * BK + (wn * WN + l32) * BK;                                    \
+    bf16x8 fa0[TM], fw0[TN], fa1[TM], fw1[TN];                                                                    \
+    SPECA_LDFRAG(fa0, fw0, 0);                                                                                    \
+    SPECA_LDFRAG(fa1, fw1, 1);                                                                                    \
+    SPECA_LOADS(new_, (ktl_) < nk ? (ktl_) : nk - 1);                                                             \
+    SPECA_MFMAS(fa0, fw0);                                                                                        \
+    SPECA_LDFRAG(fa0, fw0, 2);                                                                                    \
+    SPECA_MFMAS(fa1, fw1);                                                                                        \
+    SPECA_LDFRAG(fa1, fw1, 3);                                                                                    \
+    SPECA_MFMAS(fa0, fw0);                                                                                        \
+    SPECA_MFMAS(fa1, fw1);                                                                                        \
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * (TM + TN), 0);                                                \
+    SPECA_SLICE_GROUPS;                                                                                           \
+    __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);                                                      \
+    SPECA_SLICE_GROUPS;                                                                                           \
+    __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);                                                      \
+    SPECA_SLICE_GROUPS;                                                                                           \
+    SPECA_SLICE_GROUPS;                                                                                           \
+  }
   constexpr int WAIT_VM0 = 0x0F70;                           // s_waitcnt vmcnt(0), other counters untouched
   // prologue: steps 0 .. NS-2, each by its loader waves
 #pragma unroll
@@ -450,8 +502,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t
     const bool mine_ = NS == 2 || grp == (par_);             /* wave-uniform */                                    \
     if (mine_) __builtin_amdgcn_s_waitcnt(WAIT_VM0);         /* my only outstanding loads are those of this step */ \
     __builtin_amdgcn_s_barrier();                                                                                 \
-    if (mine_ && (kt_) + NS - 1 < nk) SPECA_LOADS(new_, (kt_) + NS - 1);                                          \
-    SPECA_COMPUTE(cur_);                                                                                          \
+    if (SPREAD) {                                                                                                 \
+      if (mine_) SPECA_COMPUTE_L(cur_, new_, (kt_) + NS - 1)                                                      \
+      else SPECA_COMPUTE(cur_)                                                                                    \
+    } else {                                                                                                      \
+      if (mine_ && (kt_) + NS - 1 < nk) SPECA_LOADS(new_, (kt_) + NS - 1);                                        \
+      SPECA_COMPUTE(cur_);                                                                                        \
+    }                                                                                                             \
   }
   if (NS == 2) {
     for (int kt = 0; kt < nk; kt += 2) {
@@ -471,6 +528,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t
 #undef SPECA_STEP
   __builtin_amdgcn_s_waitcnt(WAIT_VM0);                      // nothing is outstanding here; kept as a guard before LDS is reused
 #undef SPECA_COMPUTE
+#undef SPECA_COMPUTE_L
+#undef SPECA_SLICE_GROUPS
 #undef SPECA_MFMAS
 #undef SPECA_LDFRAG
 #undef SPECA_LOADS
