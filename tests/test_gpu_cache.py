@@ -249,14 +249,16 @@ def test_error_paths():
     ctx.close()
 
 
-def test_config2_full_size_sampled():
+@pytest.mark.parametrize("layout", ["differences", "ring"])
+def test_config2_full_size_sampled(layout):
     """Configuration 2 at full size (28 slots x 8 x 256 x 1152, bf16, order 2, references at
-    steps 0,4,8), in the launch shape the benchmark times; checked on sampled positions."""
+    steps 0,4,8), in the launch shape the benchmark times (both cache layouts; the benchmark
+    runs the ring); checked on sampled positions."""
     sp = _sp()
     from paper_2509_11628_amd import binding as bd
     slots, B, T, D, m = 28, 8, 256, 1152, 2
     ctx = sp.Context(sp.cache_only_desc(slots, T, D, bd.BF16))
-    ctx.init_cache(sp.make_cfg(order=m, interval=4), B)
+    ctx.init_cache(sp.make_cfg(order=m, interval=4, layout=bd.CACHE_RING if layout == "ring" else bd.CACHE_DIFFERENCES), B)
     rows = list(range(B))
     feats = si.feature_trajectory(slots, B, T, D, [0, 4, 8], seed=0, dtype="bf16")
     for s, f in zip([0, 4, 8], feats):
@@ -271,12 +273,12 @@ def test_config2_full_size_sampled():
     for k in (1, 2, 3):
         ctx.forecast(8 + k, rows, out)
         got = _host(out[idx[0], idx[1], idx[2], idx[3]])
-        c = core.FeatureCache(1, m, "taylor", "bf16")
+        c = core.make_cache(layout, 1, m, "taylor", "bf16")
         for s, f in zip([0, 4, 8], F):
             c.refresh(s, [f])
         expb = core.bf16_round(c.forecast(8 + k, 0))
-        assert np.all(np.abs(got - expb) <= np.abs(expb) * 2.0 ** -7 + 1e-30)
-        assert np.mean(got != expb) < 0.02
+        assert np.all(np.abs(got - expb) <= np.abs(expb) * 2.0 ** -7 + (1e-5 if layout == "ring" else 1e-30))
+        assert np.mean(got != expb) < (0.03 if layout == "ring" else 0.02)
     # verification on the last slot against the recipe's perturbed target: 4 accept / 4 reject at 0.05
     pred = _host(out[slots - 1]).astype(np.float32)
     truth = si.perturbed_target(pred, si.VERIFY_DELTAS, seed=0, dtype="bf16")
