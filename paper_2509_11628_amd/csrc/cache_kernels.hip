@@ -54,6 +54,22 @@ template <typename T>
 __device__ inline typename Vec<T>::raw ldg(const T* p) {
   return *reinterpret_cast<const typename Vec<T>::raw*>(p);
 }
+// 16-byte streaming forms: the cache planes and the materialised forecast are touched once per step and are far
+// larger than any cache level, so they are marked non-temporal (measured +2..3 % on the forecast kernels).
+typedef unsigned int stream_u32x4 __attribute__((ext_vector_type(4)));
+template <typename T>
+__device__ inline typename Vec<T>::raw ldg_stream(const T* p) {
+  const stream_u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const stream_u32x4*>(p));
+  typename Vec<T>::raw o;
+  __builtin_memcpy(&o, &r, 16);
+  return o;
+}
+template <typename T>
+__device__ inline void stg_stream(T* p, const typename Vec<T>::raw& v) {
+  stream_u32x4 r;
+  __builtin_memcpy(&r, &v, 16);
+  __builtin_nontemporal_store(r, reinterpret_cast<stream_u32x4*>(p));
+}
 template <typename T>
 __device__ inline void stg(T* p, const typename Vec<T>::raw& v) {
   *reinterpret_cast<typename Vec<T>::raw*>(p) = v;
@@ -83,7 +99,7 @@ __global__ __launch_bounds__(kThreads) void forecast_kernel(CacheGeom g, RowTabl
       typename Vec<T>::raw r[NT];
 #pragma unroll
       for (int o = 0; o < NT; ++o)
-        if (o <= order) r[o] = ldg(src[o] + v * V);
+        if (o <= order) r[o] = ldg_stream(src[o] + v * V);
       float acc[V];
 #pragma unroll
       for (int e = 0; e < V; ++e) acc[e] = 0.0f;
@@ -95,7 +111,7 @@ __global__ __launch_bounds__(kThreads) void forecast_kernel(CacheGeom g, RowTabl
 #pragma unroll
           for (int e = 0; e < V; ++e) acc[e] = fmaf(c[o], f[e], acc[e]);
         }
-      stg(dst + v * V, Vec<T>::pack(acc));
+      stg_stream(dst + v * V, Vec<T>::pack(acc));
     }
   } else {
     for (int64_t e = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; e < g.E;
@@ -128,14 +144,14 @@ __global__ __launch_bounds__(kThreads) void refresh_kernel(CacheGeom g, RowTable
     const int64_t nvec = g.E / V;
     for (int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; v < nvec;
          v += static_cast<int64_t>(gridDim.x) * kThreads) {
-      typename Vec<T>::raw rf = ldg(f + v * V);
+      typename Vec<T>::raw rf = ldg_stream(f + v * V);
       typename Vec<T>::raw ro[NT];
 #pragma unroll
       for (int o = 0; o + 1 < NT; ++o)
-        if (o < order) ro[o] = ldg(d[o] + v * V);
+        if (o < order) ro[o] = ldg_stream(d[o] + v * V);
       float cur[V];
       Vec<T>::unpack(rf, cur);
-      stg(d[0] + v * V, rf);
+      stg_stream(d[0] + v * V, rf);
 #pragma unroll
       for (int o = 1; o < NT; ++o)
         if (o <= order) {
@@ -144,7 +160,7 @@ __global__ __launch_bounds__(kThreads) void refresh_kernel(CacheGeom g, RowTable
           const float inv = rt.w[i][o - 1];
 #pragma unroll
           for (int e = 0; e < V; ++e) cur[e] = (cur[e] - old[e]) * inv;
-          stg(d[o] + v * V, Vec<T>::pack(cur));
+          stg_stream(d[o] + v * V, Vec<T>::pack(cur));
         }
     }
   } else {

@@ -212,7 +212,7 @@ __global__ __launch_bounds__(256) void forecast_fold_kernel(CacheGeom g, RowTabl
       float t8[V];
       const T* p = base + g.offset(slot, oc[o], row) + e;
       if (sizeof(T) == 2) {
-        const u32x4 r = *reinterpret_cast<const u32x4*>(p);
+        const u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));     // read once per step: keep it out of the caches' way
 #pragma unroll
         for (int q = 0; q < 4; ++q) { t8[2 * q] = __uint_as_float(r[q] << 16); t8[2 * q + 1] = __uint_as_float(r[q] & 0xFFFF0000u); }
       } else {
