@@ -38,7 +38,8 @@ PEAK_HBM_GBPS = 8000.0         # MI355X HBM3E
 # same counters; launch-weighted over the kernels of the class).  Counters cannot be read from
 # inside the process, so the figures are carried here; profiles/hbm_counters.txt holds the runs.
 MEASURED_TRAFFIC = {
-    ("dit_xl2", "gemm"): 119.8e6,
+    ("dit_xl2", "gemm"): 119.8e6,                 # ring layout of the cache (the default)
+    ("dit_xl2", "gemm", "differences"): 134.1e6,
     ("forecast", "forecast"): 528.5e6,
 }
 
@@ -339,7 +340,7 @@ def main():
     else:
         ach = p["bytes"] / (p["ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS, "traffic": None}
-    roof["traffic"] = MEASURED_TRAFFIC.get(("dit_xl2", dom))
+    roof["traffic"] = MEASURED_TRAFFIC.get(("dit_xl2", dom, args.layout), MEASURED_TRAFFIC.get(("dit_xl2", dom)) if args.layout == "ring" else None)
     roof["measured_on"] = "same trajectory, row groups run serially on one stream (per-kernel event times need no overlap); value is timed with lanes"
     roof.update({"kernel": dom, "launches": p["launches"], "avg_launch_us": 1e3 * p["ms"] / max(p["launches"], 1),
                  "flops_per_launch": p["flops"] / max(p["launches"], 1), "bytes_per_launch": p["bytes"] / max(p["launches"], 1)})
