@@ -13,38 +13,73 @@ template <typename T> __device__ inline void stf(T* p, float v);
 template <> __device__ inline void stf<float>(float* p, float v) { *p = v; }
 template <> __device__ inline void stf<bf16_t>(bf16_t* p, float v) { p->bits = f32_to_bf16(v); }
 
-// One wave per (token, head); lane i owns the rotation pair (2i, 2i+1) of q and of k.
+// two consecutive elements at an even element offset
+__device__ inline void ld_pair(const float* p, float& a, float& b) { const float2 v = *reinterpret_cast<const float2*>(p); a = v.x; b = v.y; }
+__device__ inline void ld_pair(const bf16_t* p, float& a, float& b) {
+  const uint32_t v = *reinterpret_cast<const uint32_t*>(p);
+  a = __uint_as_float(v << 16); b = __uint_as_float(v & 0xFFFF0000u);
+}
+__device__ inline void st_pair(float* p, float a, float b) { *reinterpret_cast<float2*>(p) = make_float2(a, b); }
+__device__ inline void st_pair(bf16_t* p, float a, float b) {
+  *reinterpret_cast<uint32_t*>(p) = static_cast<uint32_t>(f32_to_bf16(a)) | (static_cast<uint32_t>(f32_to_bf16(b)) << 16);
+}
+
+// One wave per (token, group of HG heads); lane i owns the rotation pair (2i, 2i+1) of q and of k of each head.
+// The HG heads are independent chains (load, reduce, scale, rotate, store): taking several per wave keeps that
+// many loads in flight instead of one round trip at a time.
+constexpr int kHeadGroup = 4;
 template <typename T>
 __global__ __launch_bounds__(256) void qk_norm_rope_kernel(T* __restrict__ qkv, int64_t ld, int64_t n_items, int tokens_per_row,
                                                            int split_tok, int H, int hd, const T* __restrict__ qn1,
                                                            const T* __restrict__ kn1, const T* __restrict__ qn2,
                                                            const T* __restrict__ kn2, const float* __restrict__ cos_t,
                                                            const float* __restrict__ sin_t) {
+  constexpr int HG = kHeadGroup;
   const int64_t item = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
   if (item >= n_items) return;
   const int lane = threadIdx.x & 63;
-  const int64_t tok = item / H;
-  const int head = static_cast<int>(item - tok * H);
+  const int groups = (H + HG - 1) / HG;
+  const int64_t tok = item / groups;
+  const int head0 = static_cast<int>(item - tok * groups) * HG;
   const int t = static_cast<int>(tok % tokens_per_row);
   const bool second = t >= split_tok;
   const int half = hd / 2;
   const bool live = lane < half;
-  T* q = qkv + tok * ld + static_cast<int64_t>(head) * hd + 2 * lane;
-  T* k = q + static_cast<int64_t>(H) * hd;
-  float q0 = 0, q1 = 0, k0 = 0, k1 = 0;
-  if (live) { q0 = ldf(q); q1 = ldf(q + 1); k0 = ldf(k); k1 = ldf(k + 1); }
-  float sq = q0 * q0 + q1 * q1, sk = k0 * k0 + k1 * k1;
+  T* q[HG];
+  float q0[HG], q1[HG], k0[HG], k1[HG];
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) { sq += __shfl_xor(sq, off, 64); sk += __shfl_xor(sk, off, 64); }
-  if (!live) return;
-  const float rq = rsqrtf(sq / static_cast<float>(hd) + 1e-6f), rk = rsqrtf(sk / static_cast<float>(hd) + 1e-6f);
+  for (int g = 0; g < HG; ++g) {
+    const int head = head0 + g < H ? head0 + g : H - 1;        // a surplus head of the last group re-reads the last head; never stored
+    q[g] = qkv + tok * ld + static_cast<int64_t>(head) * hd + 2 * lane;
+    q0[g] = q1[g] = k0[g] = k1[g] = 0.0f;
+    if (live) { ld_pair(q[g], q0[g], q1[g]); ld_pair(q[g] + static_cast<int64_t>(H) * hd, k0[g], k1[g]); }
+  }
   const T* qn = second ? qn2 : qn1;
   const T* kn = second ? kn2 : kn1;
-  q0 *= rq * ldf(qn + 2 * lane); q1 *= rq * ldf(qn + 2 * lane + 1);
-  k0 *= rk * ldf(kn + 2 * lane); k1 *= rk * ldf(kn + 2 * lane + 1);
-  const float c = cos_t[static_cast<int64_t>(t) * half + lane], s = sin_t[static_cast<int64_t>(t) * half + lane];
-  stf(q, q0 * c - q1 * s); stf(q + 1, q0 * s + q1 * c);
-  stf(k, k0 * c - k1 * s); stf(k + 1, k0 * s + k1 * c);
+  float nq0 = 0, nq1 = 0, nk0 = 0, nk1 = 0, c = 0, s = 0;
+  if (live) {
+    ld_pair(qn + 2 * lane, nq0, nq1);
+    ld_pair(kn + 2 * lane, nk0, nk1);
+    c = cos_t[static_cast<int64_t>(t) * half + lane];
+    s = sin_t[static_cast<int64_t>(t) * half + lane];
+  }
+  float sq[HG], sk[HG];
+#pragma unroll
+  for (int g = 0; g < HG; ++g) { sq[g] = q0[g] * q0[g] + q1[g] * q1[g]; sk[g] = k0[g] * k0[g] + k1[g] * k1[g]; }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1)
+#pragma unroll
+    for (int g = 0; g < HG; ++g) { sq[g] += __shfl_xor(sq[g], off, 64); sk[g] += __shfl_xor(sk[g], off, 64); }
+  if (!live) return;
+#pragma unroll
+  for (int g = 0; g < HG; ++g) {
+    if (head0 + g >= H) break;
+    const float rq = rsqrtf(sq[g] / static_cast<float>(hd) + 1e-6f), rk = rsqrtf(sk[g] / static_cast<float>(hd) + 1e-6f);
+    const float a0 = q0[g] * (rq * nq0), a1 = q1[g] * (rq * nq1);
+    const float b0 = k0[g] * (rk * nk0), b1 = k1[g] * (rk * nk1);
+    st_pair(q[g], a0 * c - a1 * s, a0 * s + a1 * c);
+    st_pair(q[g] + static_cast<int64_t>(H) * hd, b0 * c - b1 * s, b0 * s + b1 * c);
+  }
 }
 
 template <typename T>
@@ -104,7 +139,11 @@ Error launch_qk_norm_rope(int dtype, void* qkv, int64_t ld, int64_t n_tokens, in
                           const void* qn1, const void* kn1, const void* qn2, const void* kn2, const float* cos_t, const float* sin_t,
                           hipStream_t st) {
   if (hd % 2 || hd > 128 || hd < 2) SPECA_FAIL(SPECA_EUNSUPPORTED, "qk_norm_rope: head_dim %d", hd);
-  const int64_t items = n_tokens * H;
+  // the kernel moves rotation pairs as one 4- / 8-byte access
+  const uintptr_t al = reinterpret_cast<uintptr_t>(qkv) | reinterpret_cast<uintptr_t>(qn1) | reinterpret_cast<uintptr_t>(kn1) |
+                       reinterpret_cast<uintptr_t>(qn2) | reinterpret_cast<uintptr_t>(kn2);
+  if (ld % 2 || al % 8) SPECA_FAIL(SPECA_EUNSUPPORTED, "qk_norm_rope: operands must be 8-byte aligned with an even leading dimension");
+  const int64_t items = n_tokens * ((H + kHeadGroup - 1) / kHeadGroup);
   if (items > 4LL * 0x7FFFFFFF) SPECA_FAIL(SPECA_EINVAL, "qk_norm_rope: too many items");
   if (dtype == SPECA_BF16)
     qk_norm_rope_kernel<bf16_t><<<nblk(items, 4), 256, 0, st>>>(static_cast<bf16_t*>(qkv), ld, items, tokens_per_row, split_tok, H, hd,
