@@ -449,6 +449,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t
   // Only with the 3-stage ring: there a load has two K-steps to land; with two stages (one step of lead) issuing
   // the loads later in the step cost more at the next wait than the burst did (measured -3..-5 %).
   constexpr bool SPREAD = NS == 3 && LPW % 4 == 0 && ((TM * TN) % (LPW / 4) == 0 || LPW / 4 == 3) && SPECA_SPREAD_LOADS;
+#ifndef SPECA_FINE_READS
+#define SPECA_FINE_READS 1
+#endif
 #ifndef SPECA_EARLY_LOADS
 #define SPECA_EARLY_LOADS 1
 #endif
@@ -496,6 +499,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t
         __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                                        \
       }                                                                                                           \
       if (TM * TN - L0_ > 0) __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - L0_, 0);                       \
+      if (SPECA_FINE_READS && L1_ == 0 && TM + TN <= TM * TN) {                                                   \
+        /* the next slice's fragment reads go one per MFMA too */                                                 \
+        _Pragma("unroll") for (int q = 0; q < 2; ++q) {                                                           \
+          _Pragma("unroll") for (int l = 0; l < TM + TN; ++l) {                                                   \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                    \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                    \
+          }                                                                                                       \
+          if (TM * TN - (TM + TN) > 0) __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);       \
+        }                                                                                                         \
+        __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);                                                  \
+      } else {                                                                                                    \
       __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);                                                    \
       _Pragma("unroll") for (int l = 0; l < L1_; ++l) {                                                           \
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                        \
@@ -505,13 +519,29 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t
       if (TM * TN - L1_ > 0) __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - L1_, 0);                       \
       __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);                                                    \
       __builtin_amdgcn_sched_group_barrier(0x008, 2 * TM * TN, 0);                                                \
+      }                                                                                                           \
     } else {                                                                                                      \
     SPECA_SLICE_GROUPS;                                                                                           \
+    if (SPECA_FINE_READS && LPW / 4 == 3 && TM * TN == 4 && TM + TN == 4) {                                       \
+      /* slices 1 and 2: the fragment reads of the slice after next go one per MFMA as well */                    \
+      _Pragma("unroll") for (int q = 0; q < 2; ++q) {                                                             \
+        _Pragma("unroll") for (int l = 0; l < 3; ++l) {                                                           \
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                      \
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                      \
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);                                                      \
+          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                                      \
+        }                                                                                                         \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                        \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                        \
+      }                                                                                                           \
+      SPECA_SLICE_GROUPS;                                                                                         \
+    } else {                                                                                                      \
     __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);                                                      \
     SPECA_SLICE_GROUPS;                                                                                           \
     __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);                                                      \
     SPECA_SLICE_GROUPS;                                                                                           \
     SPECA_SLICE_GROUPS;                                                                                           \
+    }                                                                                                             \
     }                                                                                                             \
   }
   constexpr int WAIT_VM0 = 0x0F70;                           // s_waitcnt vmcnt(0), other counters untouched
