@@ -449,6 +449,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t
   // Only with the 3-stage ring: there a load has two K-steps to land; with two stages (one step of lead) issuing
   // the loads later in the step cost more at the next wait than the burst did (measured -3..-5 %).
   constexpr bool SPREAD = NS == 3 && LPW % 4 == 0 && ((TM * TN) % (LPW / 4) == 0 || LPW / 4 == 3) && SPECA_SPREAD_LOADS;
+#ifndef SPECA_ONE_AHEAD
+#define SPECA_ONE_AHEAD 1
+#endif
 #ifndef SPECA_FINE_READS
 #define SPECA_FINE_READS 1
 #endif
@@ -490,6 +493,21 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t
     SPECA_LDFRAG(fa1, fw1, 3);                                                                                    \
     SPECA_MFMAS(fa0, fw0);                                                                                        \
     SPECA_MFMAS(fa1, fw1);                                                                                        \
+    if (EARLY && SPECA_ONE_AHEAD && LPW <= TM * TN && TM + TN <= TM * TN) {                                       \
+      /* one slice of fragments ahead is enough when its reads go out one per MFMA of the current slice */        \
+      __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);                                                    \
+      _Pragma("unroll") for (int l = 0; l < TM * TN; ++l) {                                                       \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                        \
+        if (l < LPW) { __builtin_amdgcn_sched_group_barrier(0x002, 4, 0); __builtin_amdgcn_sched_group_barrier(0x020, 1, 0); } \
+        if (l < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                       \
+      }                                                                                                           \
+      _Pragma("unroll") for (int q = 0; q < 2; ++q)                                                               \
+        _Pragma("unroll") for (int l = 0; l < TM * TN; ++l) {                                                     \
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                      \
+          if (l < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                     \
+        }                                                                                                         \
+      __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);                                                    \
+    } else {                                                                                                      \
     __builtin_amdgcn_sched_group_barrier(0x100, 2 * (TM + TN), 0);                                                \
     if (EARLY) {                                                                                                  \
       constexpr int L0_ = LPW < TM * TN ? LPW : TM * TN, L1_ = LPW - L0_;   /* loads placed in slices 0 and 1 */     \
@@ -541,6 +559,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dlds_kernel(const uint16_t
     __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);                                                      \
     SPECA_SLICE_GROUPS;                                                                                           \
     SPECA_SLICE_GROUPS;                                                                                           \
+    }                                                                                                             \
     }                                                                                                             \
     }                                                                                                             \
   }
