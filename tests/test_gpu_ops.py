@@ -42,6 +42,9 @@ SHAPES = [  # M, N, K
     (300, 16, 64),
     # the direct-to-LDS tiles, each with ragged M and N: 128x128, 256x128 (3-stage ring, K-steps 3n+1 and 3n+2), 256x256
     (1000, 3304, 128), (4000, 1160, 256), (4000, 1160, 320), (4000, 3400, 2048),
+    # one and two K-steps (the rings re-read the last tile into a free stage past the end of K): 3-stage and 2-stage
+    # 256x128, and the shortest K the 256x256 tile takes
+    (4096, 3456, 64), (4000, 1160, 64), (4096, 3456, 128), (4608, 3072, 2048),
 ]
 
 
