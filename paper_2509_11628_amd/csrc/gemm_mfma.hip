@@ -717,6 +717,9 @@ Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, i
   static const bool staged_only = [] { const char* e = getenv("SPECA_GEMM_LOOP"); return e && e[0] == 's'; }();
   if (K % BK == 0 && M >= 256 && !staged_only) {
     if (K >= 2048 && t256s >= 160) return launch_dlds<256, 256, 4, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
+    // shorter K: only when the tiles are one wave of the chip at most (the 4096 x 3456 x 1152 qkv GEMM: 216 tiles, 842 against
+    // 668 TFLOP/s; at 288 tiles the second, nearly empty wave costs more than the tile saves)
+    if (K >= 1024 && t256s >= 160 && t256s <= 256) return launch_dlds<256, 256, 4, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
     if (t256 >= 100 && t128 <= 1024) {      // 100: the 1024 x 3456 qkv GEMM of a four-lane step (108 tiles) belongs here, measured
       // at most one tile per CU and a short K loop: the 2-stage ring (96 KiB of LDS leave room for a block of
       // another launch on the same CU when row groups run side by side); otherwise two loader groups, 3 stages
