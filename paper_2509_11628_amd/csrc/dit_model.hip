@@ -172,6 +172,7 @@ struct DiT final : Model {
   struct Lane {
     hipStream_t st;
     int o;
+    int shared = 0;     // other lanes run beside this one
   };
   const float* mod_at(int l, int which, int o = 0) const {
     return mod + static_cast<int64_t>(o) * mod_n + static_cast<int64_t>(l) * 6 * D + static_cast<int64_t>(which) * D;
@@ -243,6 +244,7 @@ struct DiT final : Model {
     }
     GemmEpi b;
     b.bias = blk[l].fc2_b;
+    b.shared_chip = ln.shared;
     if (truth_out) {
       b.mode = EPI_F32; b.out = truth_out + ln.o * TD; b.ldo = D;
     } else {
@@ -265,11 +267,11 @@ struct DiT final : Model {
     Error body = [&]() -> Error {
       for (int l = l0; l < l1; ++l) {
         for (int k = 0; k < ls.n_lanes; ++k) {
-          const Lane ln{ctx->lane_stream[k], ls.first[k]};
+          const Lane ln{ctx->lane_stream[k], ls.first[k], ls.n_lanes > 1 ? 1 : 0};
           SPECA_TRY(attn_branch(ctx, ln, l, hs, ls.first[k + 1] - ls.first[k], refresh_rt ? &sub[k] : nullptr));
         }
         for (int k = 0; k < ls.n_lanes; ++k) {
-          const Lane ln{ctx->lane_stream[k], ls.first[k]};
+          const Lane ln{ctx->lane_stream[k], ls.first[k], ls.n_lanes > 1 ? 1 : 0};
           SPECA_TRY(mlp_branch(ctx, ln, l, hs, ls.first[k + 1] - ls.first[k], refresh_rt ? &sub[k] : nullptr,
                                l == l1 - 1 ? truth_last_mlp : nullptr));
         }

@@ -22,6 +22,8 @@ struct GemmEpi {
   const void* bias = nullptr;     // [N] model dtype
   void* out = nullptr;            // STORE/GELU/SILU/F32 destination
   int64_t ldo = 0;
+  int shared_chip = 0;            // dispatch hint: other launches run beside this one (row groups side by side), so a
+                                  // launch of few, high-intensity tiles does not leave the rest of the chip idle
   // EPI_BRANCH
   float* h = nullptr;             // [M][N] fp32 residual stream
   int64_t ldh = 0;

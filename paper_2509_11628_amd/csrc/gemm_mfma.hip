@@ -735,6 +735,10 @@ Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, i
     // shorter K: only when the tiles are one wave of the chip at most (the 4096 x 3456 x 1152 qkv GEMM: 216 tiles, 842 against
     // 668 TFLOP/s; at 288 tiles the second, nearly empty wave costs more than the tile saves)
     if (K >= 1024 && t256s >= 160 && t256s <= 256) return launch_dlds<256, 256, 4, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
+    // long K with few tiles while other launches fill the remaining CUs (the 1024 x 1152 x 4608 fc2 GEMM of a four-lane step):
+    // the higher-intensity tile wins (+1 % on configuration 3 with lanes; alone on the chip it loses: -2.5 % on the
+    // text-stream GEMMs of the FLUX shape)
+    if (epi.shared_chip && K >= 2048 && t256 >= 32 && t256 < 100) return launch_dlds<256, 128, 4, 2, 3>(A, lda, W, ldw, M, N, K, epi, st);
     if (t256 >= 100 && t128 <= 1024) {      // 100: the 1024 x 3456 qkv GEMM of a four-lane step (108 tiles) belongs here, measured
       // at most one tile per CU and a short K loop: the 2-stage ring (96 KiB of LDS leave room for a block of
       // another launch on the same CU when row groups run side by side); otherwise two loader groups, 3 stages
