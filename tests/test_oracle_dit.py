@@ -152,3 +152,83 @@ def test_flop_count_matches_paper_table():
     m = dit.DiTOracle(si.dit_xl2(), {})
     per_pair = 2 * m.flops_per_row()
     assert per_pair / 1e12 == pytest.approx(23.74 / 50, rel=5e-3)
+
+
+def _torch_conditioning(s, w, t, labels):
+    """c = MLP_t(sinusoid(t)) + y_table[label] from library routines: torch.cos/sin of the angles written
+    out frequency by frequency, F.linear, F.silu, F.embedding."""
+    T64 = lambda a: torch.tensor(np.asarray(a, dtype=np.float64))
+    half = s.freq_dim // 2
+    ang = torch.tensor([[float(t) * 10000.0 ** (-j / half) for j in range(half)]] * len(labels), dtype=torch.float64)
+    emb = torch.cat([torch.cos(ang), torch.sin(ang)], dim=1)
+    temb = F.linear(F.silu(F.linear(emb, T64(w["t_w1"]), T64(w["t_b1"]))), T64(w["t_w2"]), T64(w["t_b2"]))
+    return (temb + F.embedding(torch.tensor(list(labels), dtype=torch.long), T64(w["y_table"]))).numpy()
+
+
+def _torch_final(s, w, h, c):
+    """(shift, scale) = chunk(Linear(SiLU(c)), 2); Linear(LN(h)(1+scale)+shift); un-patchify by explicit
+    indexing: out[r, ch, i p + pi, j p + pj] = tok[r, i g + j, (ch p + pi) p + pj]."""
+    T64 = lambda a: torch.tensor(np.asarray(a, dtype=np.float64))
+    D, p, g, C = s.hidden, s.patch, s.grid, s.in_channels
+    mod = F.linear(F.silu(T64(c)), T64(w["fmod_w"]), T64(w["fmod_b"]))
+    shift, scale = mod[:, None, :D], mod[:, None, D:]
+    tok = F.linear(F.layer_norm(T64(h), (D,), eps=1e-6) * (1 + scale) + shift, T64(w["final_w"]), T64(w["final_b"])).numpy()
+    out = np.zeros((h.shape[0], C, g * p, g * p))
+    for i in range(g):
+        for j in range(g):
+            for ch in range(C):
+                for pi in range(p):
+                    for pj in range(p):
+                        out[:, ch, i * p + pi, j * p + pj] = tok[:, i * g + j, (ch * p + pi) * p + pj]
+    return out
+
+
+def test_conditioning_vs_library_assembly():
+    s = si.dit_tiny()
+    w = si.make_dit_weights(s, seed=5, std=0.2)          # every bias and table row matters at this scale
+    m = dit.DiTOracle(s, w)
+    labels = [0, 3, s.num_classes, 3]                    # includes the null row and a repeated label
+    for t in (0.0, 1.0, 417.0, 980.0):
+        got = m.conditioning(t, labels)
+        np.testing.assert_allclose(got, _torch_conditioning(s, w, t, labels), rtol=1e-10, atol=1e-12)
+    # what a plausible mistake changes: dropping a bias, the wrong table row, sin before cos
+    c = m.conditioning(417.0, labels)
+    assert np.max(np.abs(c[1] - c[3])) == 0.0 and np.max(np.abs(c[0] - c[1])) > 1e-2
+    w2 = dict(w); w2["t_b2"] = np.zeros_like(w["t_b2"])
+    assert np.max(np.abs(dit.DiTOracle(s, w2).conditioning(417.0, labels) - c)) > 1e-2
+    w3 = dict(w); w3["t_w1"] = np.concatenate([w["t_w1"][:, s.freq_dim // 2:], w["t_w1"][:, : s.freq_dim // 2]], axis=1)
+    assert np.max(np.abs(dit.DiTOracle(s, w3).conditioning(417.0, labels) - c)) > 1e-2
+    # t = 0: the embedding is (1,..,1,0,..,0), so only the cosine half of t_w1 enters
+    half = s.freq_dim // 2
+    e0 = w["t_w1"][:, :half].astype(np.float64).sum(axis=1) + w["t_b1"]
+    c0 = (e0 / (1 + np.exp(-e0))) @ w["t_w2"].astype(np.float64).T + w["t_b2"] + w["y_table"][3]
+    np.testing.assert_allclose(m.conditioning(0.0, [3])[0], c0, rtol=1e-10, atol=1e-12)
+
+
+def test_final_layer_vs_library_assembly():
+    s = si.dit_tiny()
+    w = si.make_dit_weights(s, seed=6, std=0.2)
+    m = dit.DiTOracle(s, w)
+    x = si.make_latents(3, s.in_channels, s.latent_hw, seed=6)
+    h, c = m.begin(x, 250.0, [1, 2, s.num_classes])
+    got = m.final(h, c)
+    ref = _torch_final(s, w, h, c)
+    assert got.shape == x.shape
+    np.testing.assert_allclose(got, ref, rtol=1e-9, atol=1e-11)
+    # the (shift, scale) order matters at this weight scale: the swapped split is far from the reference
+    D = s.hidden
+    w_sw = dict(w)
+    w_sw["fmod_w"] = np.concatenate([w["fmod_w"][D:], w["fmod_w"][:D]])
+    w_sw["fmod_b"] = np.concatenate([w["fmod_b"][D:], w["fmod_b"][:D]])
+    assert np.max(np.abs(dit.DiTOracle(s, w_sw).final(h, c) - ref)) > 1e-2 * np.max(np.abs(ref))
+    # zero modulation: a plain LayerNorm + linear layer
+    w0 = dict(w); w0["fmod_w"] = np.zeros_like(w["fmod_w"]); w0["fmod_b"] = np.zeros_like(w["fmod_b"])
+    tok = F.linear(F.layer_norm(torch.tensor(h), (D,), eps=1e-6), torch.tensor(w["final_w"], dtype=torch.float64),
+                   torch.tensor(w["final_b"], dtype=torch.float64)).numpy()
+    np.testing.assert_allclose(dit.DiTOracle(s, w0).final(h, c), m.unpatchify(tok), rtol=1e-10, atol=1e-12)
+    # forward = begin -> blocks -> final, with nothing else in between
+    out, _ = m.forward(x, 250.0, [1, 2, s.num_classes])
+    hh = h
+    for l in range(s.depth):
+        hh, _ = m.block_real(l, hh, c)
+    np.testing.assert_allclose(out, _torch_final(s, w, hh, c), rtol=1e-9, atol=1e-11)

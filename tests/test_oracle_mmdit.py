@@ -161,3 +161,66 @@ def test_flow_trajectory_tau_zero_is_plain_sampling_and_schedules():
     assert tr.kind[0].tolist() == [0, 1, 1, 0, 1, 1, 0, 1]
     out, tr = sampler.sample(m, sampler.SpecaConfig(order=1, interval=4), sol, core.tau_linear(0.02, 0.004, S), x, conds)
     assert (tr.kind == 1).sum() > 0 and (tr.kind == 2).sum() > 0
+
+
+def _torch_mm_conditioning(s, w, t, pooled):
+    """vec = MLP_t(sinusoid(t)) + MLP_v(pooled) from library routines, angles written out frequency by frequency."""
+    half = s.freq_dim // 2
+    ang = torch.tensor([[float(t) * 10000.0 ** (-j / half) for j in range(half)]] * pooled.shape[0], dtype=torch.float64)
+    emb = torch.cat([torch.cos(ang), torch.sin(ang)], dim=1)
+    tv = F.linear(F.silu(F.linear(emb, T64(w["t_w1"]), T64(w["t_b1"]))), T64(w["t_w2"]), T64(w["t_b2"]))
+    pv = F.linear(F.silu(F.linear(T64(pooled), T64(w["v_w1"]), T64(w["v_b1"]))), T64(w["v_w2"]), T64(w["v_b2"]))
+    return (tv + pv).numpy()
+
+
+def _torch_mm_finish(s, w, h, vec):
+    """Final layer on the image tokens only; un-patchify by explicit indexing:
+    out[r, c, f, i p + pi, j p + pj] = tok[r, (f gh + i) gw + j, (c p + pi) p + pj]."""
+    D, p = s.hidden, s.patch
+    gh, gw = s.latent_h // p, s.latent_w // p
+    mod = F.linear(F.silu(T64(vec)), T64(w["fmod_w"]), T64(w["fmod_b"]))
+    shift, scale = mod[:, None, :D], mod[:, None, D:]
+    tok = F.linear(F.layer_norm(T64(h[:, s.txt_tokens:]), (D,), eps=1e-6) * (1 + scale) + shift, T64(w["final_w"]), T64(w["final_b"])).numpy()
+    out = np.zeros((h.shape[0], s.in_channels, s.latent_t, s.latent_h, s.latent_w))
+    for f in range(s.latent_t):
+        for i in range(gh):
+            for j in range(gw):
+                for c in range(s.in_channels):
+                    for pi in range(p):
+                        for pj in range(p):
+                            out[:, c, f, i * p + pi, j * p + pj] = tok[:, (f * gh + i) * gw + j, (c * p + pi) * p + pj]
+    return out
+
+
+@pytest.mark.parametrize("shape_fn", [si.mmdit_tiny, si.mmdit_tiny_video])
+def test_conditioning_and_finish_vs_library_assembly(shape_fn):
+    s = shape_fn()
+    w = si.make_mmdit_weights(s, 7, std=0.15)
+    m = mmdit.MMDiTOracle(s, w)
+    x = si.make_video_latents(2, s, 7); txt, pooled = si.make_text(2, s, 7)
+    for t in (0.0, 37.0, 1000.0):
+        np.testing.assert_allclose(m.conditioning(t, pooled), _torch_mm_conditioning(s, w, t, pooled), rtol=1e-10, atol=1e-12)
+    vec = m.conditioning(37.0, pooled)
+    # both halves enter: another pooled vector or another timestep changes the result; a dropped bias does too
+    assert np.max(np.abs(m.conditioning(38.0, pooled) - vec)) > 1e-4 and np.max(np.abs(m.conditioning(37.0, pooled[::-1]) - vec)) > 1e-3
+    w2 = dict(w); w2["v_b2"] = np.zeros_like(w["v_b2"])
+    assert np.max(np.abs(mmdit.MMDiTOracle(s, w2).conditioning(37.0, pooled) - vec)) > 1e-2
+    h, vec = m.begin(x, 37.0, (txt, pooled))
+    got = m.finish(h, vec)
+    ref = _torch_mm_finish(s, w, h, vec)
+    assert got.shape == x.shape
+    np.testing.assert_allclose(got, ref, rtol=1e-9, atol=1e-11)
+    # the text rows never reach the output of the final layer
+    h2 = h.copy(); h2[:, : s.txt_tokens] += 1.0
+    np.testing.assert_array_equal(m.finish(h2, vec), got)
+    # swapped (shift, scale) is far from the reference
+    D = s.hidden
+    w_sw = dict(w)
+    w_sw["fmod_w"] = np.concatenate([w["fmod_w"][D:], w["fmod_w"][:D]]); w_sw["fmod_b"] = np.concatenate([w["fmod_b"][D:], w["fmod_b"][:D]])
+    assert np.max(np.abs(mmdit.MMDiTOracle(s, w_sw).finish(h, vec) - ref)) > 1e-2 * np.max(np.abs(ref))
+    # forward = begin -> blocks -> finish
+    out, _ = m.forward(x, 37.0, (txt, pooled))
+    hh = h
+    for b in range(m.n_blocks):
+        hh, _ = m.block_real(b, hh, vec)
+    np.testing.assert_allclose(out, _torch_mm_finish(s, w, hh, vec), rtol=1e-9, atol=1e-11)
