@@ -101,6 +101,7 @@ class SpecaConfig:
     warmup_full: int = 1           # steps 0..warmup_full-1 are always full
     cache_store: Optional[str] = None   # None (float64) | "f32" | "bf16": storage rounding of the cache
     cache_layout: str = "differences"   # "differences" (Sec. 3.3 as described) | "ring" (raw features, same forecasts)
+    metric: str = "l2"             # "l2" (Eq. 4) | "l1" | "linf" | "cosine" (appendix "Choice of Error Metrics")
 
 
 @dataclass
@@ -145,6 +146,15 @@ def full_step(model, cache: core.FeatureCache, x_rows, t, labels, s):
     return out
 
 
+def verification_error(metric: str, pred, truth, eps: float) -> np.float32:
+    """The error the verifier compares with the threshold, rounded to float32 (the precision of the decision).
+    Eq. 4 by default; the other metrics of the appendix ablation on request."""
+    if metric == "l2":
+        return core.relative_error_f32(pred, truth, eps)
+    fn = {"l1": core.relative_error_l1, "linf": core.relative_error_linf, "cosine": core.cosine_distance}[metric]
+    return np.float32(fn(pred, truth, eps))
+
+
 def speculative_attempt(model, cache: core.FeatureCache, cfg: SpecaConfig, x_rows, t, labels, s, tau_s):
     """Steps 2-3 of the workflow for one sample at step s.
     -> (accepted, per-row errors, model output rows or None)."""
@@ -159,7 +169,7 @@ def speculative_attempt(model, cache: core.FeatureCache, cfg: SpecaConfig, x_row
     _, real = model.block_real(lv, h, c)                               # the verify block, for real
     v = first_slot[lv + 1] - 1                                         # last slot of the verify block
     Ft = real[-1]
-    errs = [core.relative_error_f32(Fp[v][r], Ft[r], cfg.eps) for r in range(Ft.shape[0])]   # Eq. 4 per row
+    errs = [verification_error(cfg.metric, Fp[v][r], Ft[r], cfg.eps) for r in range(Ft.shape[0])]   # Eq. 4 per row
     ok = all(core.accept(e, tau_s) for e in errs)
     if not ok:
         return False, errs, None

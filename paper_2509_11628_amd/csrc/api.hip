@@ -130,6 +130,7 @@ static void free_ctx(speca_ctx* ctx) {
     if (ctx->lane_join[k]) (void)hipEventDestroy(ctx->lane_join[k]);
   ctx->model.reset();
   if (ctx->geom.base) (void)hipFree(ctx->geom.base);
+  if (ctx->model_out) (void)hipFree(ctx->model_out);
   VerifyScratch& v = ctx->vs;
   if (v.tau_dev) (void)hipFree(v.tau_dev);
   if (v.err_dev) (void)hipFree(v.err_dev);
@@ -255,7 +256,23 @@ static Error init_cache_impl(speca_ctx* ctx, const speca_cfg* cfg, int batch_row
   ctx->cfg = *cfg;
   ctx->batch_rows = batch_rows;
   clear_refs(ctx);
-  if (ctx->model) SPECA_TRY(ctx->model->prepare(ctx, batch_rows));
+  if (ctx->model) {
+    SPECA_TRY(ctx->model->prepare(ctx, batch_rows));
+    const size_t mo = static_cast<size_t>(batch_rows) * ctx->model->latent_elems() * sizeof(float);
+    if (mo > ctx->model_out_cap) {
+      if (ctx->model_out) {
+        SPECA_HIP(hipStreamSynchronize(ctx->stream));
+        SPECA_HIP(hipFree(ctx->model_out));
+        ctx->model_out = nullptr;
+        ctx->model_out_cap = 0;
+      }
+      if (hipMalloc(reinterpret_cast<void**>(&ctx->model_out), mo) != hipSuccess) {
+        (void)hipGetLastError();
+        SPECA_FAIL(SPECA_ENOMEM, "cannot allocate %zu bytes for the model outputs of a step", mo);
+      }
+      ctx->model_out_cap = mo;
+    }
+  }
   ctx->cache_ready = true;
   return ok();
 }

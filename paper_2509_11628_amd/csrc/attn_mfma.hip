@@ -21,7 +21,6 @@
 // current tile's softmax); and, for T <= 256, one that holds the whole sequence of a head in LDS and takes
 // the softmax in one pass.
 // head_dim is padded with zeros to a multiple of 16 for q k^T and of 32 for P V.
-#include <cstdlib>
 #include <type_traits>
 
 #include "gemm.h"
@@ -717,15 +716,12 @@ Error launch_hd(const void* qkv, void* out, int64_t ldo, int rows, int T, int H,
     SPECA_HIP(hipGetLastError());
     return ok();
   }
-  // head_dim 128: direct-to-LDS tiles with the transposing read (SPECA_ATTN=staged keeps the register-staged kernel: A/B timing)
-  // SPECA_ATTN=staged | dma (direct-to-LDS, no overlap of scores and softmax) | pipe (default): A/B timing
-  static const int attn_mode = [] { const char* e = getenv("SPECA_ATTN"); return !e ? 2 : e[0] == 's' ? 0 : e[0] == 'd' ? 1 : 2; }();
-  if (HD == 128 && attn_mode != 0) {
+  // head_dim 128: direct-to-LDS tiles with the transposing read, scores of the next tile under the softmax
+  if (HD == 128) {
     constexpr size_t smem_d = static_cast<size_t>(4) * 64 * 128 * sizeof(uint16_t);
     dim3 grid_d((T + 127) / 128, H, rows);
     const float sl2 = 1.4426950408889634f / sqrtf(128.0f);
-    if (attn_mode == 1) attention_dma_kernel<false><<<grid_d, 256, smem_d, st>>>(static_cast<const uint16_t*>(qkv), static_cast<uint16_t*>(out), ldo, T, H, sl2);
-    else attention_dma_kernel<true><<<grid_d, 256, smem_d, st>>>(static_cast<const uint16_t*>(qkv), static_cast<uint16_t*>(out), ldo, T, H, sl2);
+    attention_dma_kernel<true><<<grid_d, 256, smem_d, st>>>(static_cast<const uint16_t*>(qkv), static_cast<uint16_t*>(out), ldo, T, H, sl2);
     SPECA_HIP(hipGetLastError());
     return ok();
   }

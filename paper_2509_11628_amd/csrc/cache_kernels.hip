@@ -9,7 +9,6 @@
 // sequence, wave shuffle tree, per-block LDS order, second pass over fixed-size chunk
 // partials), so results are bit-reproducible and do not depend on which other rows share
 // the launch.
-#include <cstdlib>
 
 #include "kernels.h"
 
@@ -428,9 +427,7 @@ Error launch_cache_warm(const CacheGeom& g, const RowTable& rt, int slot, hipStr
     if (rt.order[i] < 0 || rt.order[i] > g.m) SPECA_FAIL(SPECA_EINVAL, "cache warm: order %d", rt.order[i]);
     mo = rt.order[i] > mo ? rt.order[i] : mo;
   }
-  // SPECA_WARM=0 switches the hint off (A/B timing)
-  static const bool off = [] { const char* e = getenv("SPECA_WARM"); return e && e[0] == '0'; }();
-  if (mo == 0 || off) return ok();                            // first references: nothing old to read
+  if (mo == 0) return ok();                            // first references: nothing old to read
   const int esz = static_cast<int>(dtype_size(g.dtype));
   const int64_t bytes = g.E * esz;
   if (bytes % 16) return ok();                                // only a hint: skip odd geometries

@@ -171,8 +171,8 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 // gate of slot j for compact row i: mod[i * mod_stride + gate_off[2j + s] + d], s = 0 for elements below
 // split_elem (the text tokens of a two-stream block), 1 from there on.
 template <typename T, int NT>
-__global__ __launch_bounds__(256) void forecast_fold_kernel(CacheGeom g, RowTable rt, const float* __restrict__ h_in,
-                                                            float* __restrict__ h_out, const float* __restrict__ mod,
+__global__ __launch_bounds__(256) void forecast_fold_kernel(CacheGeom g, RowTable rt, const float* h_in,   // h_in may be h_out (in place)
+                                                            float* h_out, const float* __restrict__ mod,
                                                             int64_t mod_stride, const int32_t* __restrict__ gate_off, int64_t split_elem,
                                                             int s0, int s1, int D) {
   constexpr int V = 8;     // 8 elements per thread: 2 x 16 B of fp32 hidden, 16 B (bf16) or 2 x 16 B (fp32) of every cached tensor

@@ -1,8 +1,6 @@
 // Dispatch of the linear layers and attention to the kernel families (see gemm.h).
 #include "gemm.h"
 
-#include <cstdlib>
-
 namespace speca {
 
 Error launch_gemm_simple(int dtype, const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi,
@@ -13,12 +11,6 @@ Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, i
 
 bool attention_mfma_supported(const void* qkv, const void* out, int64_t ldo, int H, int hd);
 Error launch_attention_mfma(const void* qkv, void* out, int64_t ldo, int rows, int T, int H, int hd, hipStream_t st);
-
-// SPECA_FORCE_SIMPLE=1 routes bf16 work to the plain-FMA kernels (A/B checks of the MFMA kernels).
-static bool force_simple() {
-  static const bool v = [] { const char* e = getenv("SPECA_FORCE_SIMPLE"); return e && e[0] == '1'; }();
-  return v;
-}
 
 Error launch_gemm(int dtype, const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi,
                   hipStream_t st) {
@@ -39,14 +31,14 @@ Error launch_gemm(int dtype, const void* A, int64_t lda, const void* W, int64_t 
   } else if (!epi.out || epi.ldo < N) {
     SPECA_FAIL(SPECA_EINVAL, "gemm: output missing");
   }
-  if (dtype == SPECA_BF16 && !force_simple() && gemm_mfma_supported(A, lda, W, ldw, N, K))
+  if (dtype == SPECA_BF16 && gemm_mfma_supported(A, lda, W, ldw, N, K))
     return launch_gemm_mfma(A, lda, W, ldw, M, N, K, epi, st);
   return launch_gemm_simple(dtype, A, lda, W, ldw, M, N, K, epi, st);
 }
 
 Error launch_attention(int dtype, const void* qkv, void* out, int64_t ldo, int rows, int T, int H, int hd, hipStream_t st) {
   if (!qkv || !out || rows < 1 || T < 1 || H < 1 || ldo < static_cast<int64_t>(H) * hd || ldo % 4) SPECA_FAIL(SPECA_EINVAL, "attention: bad arguments");
-  if (dtype == SPECA_BF16 && !force_simple() && attention_mfma_supported(qkv, out, ldo, H, hd))
+  if (dtype == SPECA_BF16 && attention_mfma_supported(qkv, out, ldo, H, hd))
     return launch_attention_mfma(qkv, out, ldo, rows, T, H, hd, st);
   return launch_attention_simple(dtype, qkv, out, ldo, rows, T, H, hd, st);
 }

@@ -24,7 +24,6 @@
 //                     vmcnt(0) by the waves that issued them.  Needs K % 64 == 0.  Tiles 256x128 and 256x256 (half the L2 -> LDS
 //                     bytes per FLOP of 128x128).
 //   gemm_mfma_kernel  the register-staged loop described above: K tails, small problems.
-#include <cstdlib>
 
 #include "epilogue.h"
 #include "gemm.h"
@@ -713,13 +712,11 @@ Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, i
   const int64_t t128 = static_cast<int64_t>((M + 127) / 128) * ((N + 127) / 128);
   const int64_t t256 = static_cast<int64_t>((M + 255) / 256) * ((N + 127) / 128);
   const int64_t t256s = static_cast<int64_t>((M + 255) / 256) * ((N + 255) / 256);
-  // SPECA_GEMM_LOOP=staged keeps every shape on the register-staged loop (A/B timing of the two loops)
-  static const bool staged_only = [] { const char* e = getenv("SPECA_GEMM_LOOP"); return e && e[0] == 's'; }();
   // Short K, a little more than one wave of 256x256 tiles (the 4096 x 4608 x 1152 fc1 GEMM: 288): the columns that make
   // exactly one wave go on the large tile, the remaining columns in a second launch under the ordinary rules
   // (47 + 13 us against 78 us for the one launch on 128x128 tiles).  Column ranges only shift pointers, so this is
   // limited to the epilogues that store into `out`.
-  if (K % BK == 0 && M >= 256 && !staged_only && epi.mode != EPI_BRANCH && K >= 1024 && K < 2048 && t256s > 256 && t256s <= 320) {
+  if (K % BK == 0 && M >= 256 && epi.mode != EPI_BRANCH && K >= 1024 && K < 2048 && t256s > 256 && t256s <= 320) {
     const int tiles_m = (M + 255) / 256;
     const int n1 = (256 / tiles_m) * 256;
     if (n1 >= 256 && n1 < N) {
@@ -730,7 +727,7 @@ Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, i
       return launch_gemm_mfma(A, lda, static_cast<const uint16_t*>(W) + static_cast<int64_t>(n1) * ldw, ldw, M, N - n1, K, rest, st);
     }
   }
-  if (K % BK == 0 && M >= 256 && !staged_only) {
+  if (K % BK == 0 && M >= 256) {
     if (K >= 2048 && t256s >= 160) return launch_dlds<256, 256, 4, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
     // shorter K: only when the tiles are one wave of the chip at most (the 4096 x 3456 x 1152 qkv GEMM: 216 tiles, 842 against
     // 668 TFLOP/s; at 288 tiles the second, nearly empty wave costs more than the tile saves)

@@ -89,10 +89,9 @@ Error sample_impl(speca_ctx* ctx, float* latents, int batch, const speca_cond* c
   sched.cfg = ctx->cfg;
   sched.refs.assign(B, RefHistory());
 
-  float* model_out = nullptr;
   const int64_t n = ctx->model->latent_elems();
-  SPECA_HIP(hipMalloc(&model_out, static_cast<size_t>(ctx->batch_rows) * n * sizeof(float)));
-  struct Guard { float* p; hipStream_t s; ~Guard() { (void)hipStreamSynchronize(s); (void)hipFree(p); } } guard{model_out, ctx->stream};
+  float* model_out = ctx->model_out;           // [batch_rows][n], sized by speca_init_cache
+  if (!model_out) SPECA_FAIL(SPECA_ESTATE, "the model-output workspace is missing");
 
   std::vector<int32_t> spec(B), full(B), rows;
   std::vector<uint8_t> accept(B);

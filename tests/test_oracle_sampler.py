@@ -132,6 +132,44 @@ def test_cfg_pair_accepts_only_if_both_rows_pass():
     assert tr.err[0, 2, 0] == 0.0 and tr.err[0, 2, 1] == pytest.approx(0.5)
 
 
+def test_other_metrics_decide_the_schedule():
+    """The appendix's other error metrics in place of Eq. 4, on scripted features where every metric has a
+    hand value: the branch output of a row is (1 + 0.25 [t >= 2]) * (1, 1, 1, 1) up to step 3 (parallel to
+    the reused reference: L1 = Linf = L2 = 0.25 / 1.25 = 0.2, cosine distance 0) and changes direction at t = 4
+    (reference (1.25,)*4 against (1.25, 1.25, -1.25, -1.25): the hand values are stated where they are asserted)."""
+    class DirModel(ScriptedModel):
+        def block_real(self, l, h, c):
+            f = np.zeros_like(h)
+            v = 1.0 if c < 2 else 1.25
+            f[...] = v
+            if c >= 4:
+                f[..., 2:] = -v
+            return h + f, [f]
+    def run(metric, tau):
+        m = DirModel(None)
+        _, tr = sampler.sample(m, sampler.SpecaConfig(order=0, interval=10, metric=metric), _solver(6), np.full(6, tau, np.float32),
+                               np.zeros((1, 1, 2, 2)), [0])
+        return tr
+    # t = 1: identical (0 under every metric); t = 2: scaled by 1.25; t = 4: direction change
+    for metric in ("l2", "l1", "linf"):
+        tr = run(metric, 0.1)
+        assert tr.kind[0].tolist() == [0, 1, 2, 1, 2, 1], metric
+        assert tr.err[0, 2, 0] == pytest.approx(0.2, rel=1e-6), metric
+    # at t = 4 the reference is (1.25,)*4 and the truth (1.25, 1.25, -1.25, -1.25):
+    # L2 = sqrt(2 * 2.5^2) / sqrt(4 * 1.25^2) = sqrt(2), L1 = 5 / 5 = 1, Linf = 2.5 / 1.25 = 2
+    assert run("l2", 0.1).err[0, 4, 0] == pytest.approx(np.sqrt(2.0), rel=1e-6)
+    assert run("l1", 0.1).err[0, 4, 0] == pytest.approx(1.0, rel=1e-6)
+    assert run("linf", 0.1).err[0, 4, 0] == pytest.approx(2.0, rel=1e-6)
+    # cosine distance ignores the rescaling at t = 2 (accepted: the reference stays (1,)*4) and sees the turn at
+    # t = 4: cos = (1.25 + 1.25 - 1.25 - 1.25) / (|p||t|) = 0, distance 1
+    tr = run("cosine", 0.1)
+    assert tr.kind[0].tolist() == [0, 1, 1, 1, 2, 1]
+    assert tr.err[0, 2, 0] == pytest.approx(0.0, abs=1e-7) and tr.err[0, 4, 0] == pytest.approx(1.0, rel=1e-6)
+    # the default is Eq. 4
+    assert np.array_equal(run("l2", 0.1).err, sampler.sample(DirModel(None), sampler.SpecaConfig(order=0, interval=10), _solver(6),
+                                                             np.full(6, 0.1, np.float32), np.zeros((1, 1, 2, 2)), [0])[1].err, equal_nan=True)
+
+
 # --- solvers -----------------------------------------------------------------------------
 
 
