@@ -202,6 +202,21 @@ int speca_forecast(speca_ctx* ctx, int step, const int32_t* rows, int n_rows, vo
 int speca_verify(speca_ctx* ctx, const void* pred, const void* truth, int n_rows, int64_t elems_per_row,
                  int dtype, const float* tau_per_row, float eps, float* err_out, uint8_t* accept_out);
 
+/* For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The same reduction as speca_verify (same kernels, same fixed summation order, so the same bits)
+ * with everything on the device and nothing allocated or synchronised: tau_per_row (may be NULL: then
+ * accept_out is not written), err_out and accept_out are DEVICE arrays of n_rows owned by the caller; the call
+ * is asynchronous on the context's stream and makes no HIP allocation, free or copy.  The stage-1 partial sums
+ * live in a file-scope device array of SPECA_VERIFY_STATIC_MAX_PARTIALS x 3 floats (768 KiB, held by every GPU
+ * the library runs on until the process ends): min(n_rows, SPECA_MAX_LAUNCH_ROWS) x ceil(elems_per_row / 8192)
+ * must not exceed SPECA_VERIFY_STATIC_MAX_PARTIALS, else SPECA_EINVAL with a message and nothing is launched.
+ * Every partial is written before it is read, so nothing in the array needs clearing between calls.  All
+ * contexts on one GPU share the array: calls that overlap in time on one GPU (different streams or threads)
+ * race; calls on one stream are ordered and safe. */
+#define SPECA_VERIFY_STATIC_MAX_PARTIALS 65536
+int speca_verify_static(speca_ctx* ctx, const void* pred, const void* truth, int n_rows, int64_t elems_per_row,
+                        int dtype, const float* tau_per_row, float eps, float* err_out, uint8_t* accept_out);
+
 /* Speculative attempt (Sec. 3.2 steps 2-3) for the listed rows at `step`: forecast all
  * slots and fold them, gated by the step's own modulation, into the hidden state up to
  * the verify block; run the verify block for real; Eq. 4 between the forecast and the

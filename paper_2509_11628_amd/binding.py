@@ -94,6 +94,7 @@ def load_library() -> C.CDLL:
         "speca_full_step": [vp, vp, C.POINTER(Cond), C.c_int, i32p, C.c_int, vp],
         "speca_forecast": [vp, C.c_int, i32p, C.c_int, vp],
         "speca_verify": [vp, vp, vp, C.c_int, C.c_int64, C.c_int, f32p, C.c_float, f32p, u8p],
+        "speca_verify_static": [vp, vp, vp, C.c_int, C.c_int64, C.c_int, vp, C.c_float, vp, vp],
         "speca_spec_step": [vp, vp, C.POINTER(Cond), C.c_int, i32p, C.c_int, f32p, C.c_int, f32p, u8p, vp],
         "speca_sample": [vp, vp, C.c_int, C.POINTER(Cond), C.POINTER(Solver), f32p, C.POINTER(Trace)],
         "speca_linear": [vp, C.c_int, vp, C.c_int, C.c_int, vp, C.c_int, vp, C.c_int, vp],
@@ -123,7 +124,7 @@ def load_library() -> C.CDLL:
 
 
 EXPORTED = ["speca_create", "speca_destroy", "speca_last_error", "speca_init_cache", "speca_refresh",
-            "speca_full_step", "speca_forecast", "speca_verify", "speca_spec_step", "speca_sample",
+            "speca_full_step", "speca_forecast", "speca_verify", "speca_verify_static", "speca_spec_step", "speca_sample",
             "speca_linear", "speca_attention", "speca_set_lanes", "speca_profile_begin", "speca_profile_end",
             "speca_tau_geometric", "speca_tau_linear", "speca_coefficients", "speca_divisors",
             "speca_ring_weights", "speca_sched_create", "speca_sched_destroy", "speca_sched_plan", "speca_sched_commit",
@@ -336,6 +337,22 @@ class Context:
         self._ck(self.lib.speca_verify(self.h, C.c_void_p(pred.data_ptr()), C.c_void_p(truth.data_ptr()), n_rows, E, dtype,
                                        _p(t, C.c_float) if t is not None else None, eps, _p(err, C.c_float), _p(acc, C.c_uint8)))
         return err, (acc.astype(bool) if t is not None else None)
+
+    def verify_static(self, pred, truth, err_out, tau=None, accept_out=None, eps: float = 1e-8):
+        """speca_verify_static: tau / err_out / accept_out are device tensors (fp32, fp32, uint8) of n_rows;
+        nothing is allocated or synchronised by the library."""
+        import torch
+        n_rows = pred.shape[0]
+        E = pred.numel() // n_rows
+        dtype = BF16 if pred.dtype == torch.bfloat16 else F32
+        assert pred.dtype == truth.dtype and pred.is_contiguous() and truth.is_contiguous()
+        assert err_out.dtype == torch.float32 and err_out.numel() >= n_rows
+        assert tau is None or tau.dtype == torch.float32
+        assert accept_out is None or accept_out.dtype == torch.uint8
+        self._ck(self.lib.speca_verify_static(self.h, C.c_void_p(pred.data_ptr()), C.c_void_p(truth.data_ptr()), n_rows, E, dtype,
+                                              C.c_void_p(tau.data_ptr()) if tau is not None else None, eps,
+                                              C.c_void_p(err_out.data_ptr()),
+                                              C.c_void_p(accept_out.data_ptr()) if accept_out is not None else None))
 
     def set_lanes(self, lanes: int, profile_keeps_lanes: bool = False):
         """Row groups of a step that run side by side on streams of the library (1 = serial)."""

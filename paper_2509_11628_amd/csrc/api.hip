@@ -13,6 +13,29 @@ using namespace speca;
 
 static thread_local std::string g_create_error;
 
+// ---- reduction scratch of the entry point that allocates nothing -------------------------------------------
+// speca_verify_static keeps the stage-1 partial sums of Eq. 4 in this file-scope device array instead of a
+// hipMalloc'ed buffer.  Every GPU the library runs on holds its own copy at its own address; the name below is
+// only a host-side handle: host code uses the device address that hipGetSymbolAddress returned for the
+// current device (kept per device in g_static_partial), never the name itself.
+constexpr size_t kStaticPartialFloats = SPECA_VERIFY_STATIC_MAX_PARTIALS * 3;      // 768 KiB
+static __device__ __align__(256) float scratch[kStaticPartialFloats];
+constexpr int kMaxDevices = 64;
+static float* g_static_partial[kMaxDevices] = {};
+
+// Device address of the array on `device`, which must be the current device.
+static Error static_partial_for(int device, float** out) {
+  if (device < 0 || device >= kMaxDevices) SPECA_FAIL(SPECA_EUNSUPPORTED, "device ordinal %d", device);
+  if (!g_static_partial[device]) {
+    float* p = nullptr;
+    SPECA_HIP(hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)));
+    if (!p) SPECA_FAIL(SPECA_EHIP, "hipGetSymbolAddress returned a null address");
+    g_static_partial[device] = p;
+  }
+  *out = g_static_partial[device];
+  return ok();
+}
+
 static int finish(speca_ctx* ctx, const Error& e) {
   if (e.code != SPECA_OK && ctx) ctx->err = e.msg;
   return e.code;
@@ -164,6 +187,7 @@ static Error create_impl(speca_ctx** out, const speca_model_desc* desc, const sp
       SPECA_FAIL(SPECA_EINVAL, "model kind = %d", desc->kind);
   }
   SPECA_HIP(hipGetDevice(&ctx->device));
+  SPECA_TRY(static_partial_for(ctx->device, &ctx->static_partial));      // set-up: the device is current here
   // lane streams: default priority, not synchronising with the NULL stream; ordering is by events only
   ctx->lane_stream[0] = ctx->stream;
   for (int k = 1; k < kMaxLanes; ++k) SPECA_HIP(hipStreamCreateWithFlags(&ctx->lane_stream[k], hipStreamNonBlocking));
@@ -341,6 +365,34 @@ static Error verify_impl(speca_ctx* ctx, const void* pred, const void* truth, in
   return ok();
 }
 
+// Eq. 4 with device-side inputs and outputs and the file-scope scratch: no allocation, no synchronisation.
+static Error verify_static_impl(speca_ctx* ctx, const void* pred, const void* truth, int n_rows, int64_t E, int dtype,
+                                const float* tau_dev, float eps, float* err_dev, uint8_t* accept_dev) {
+  if (!pred || !truth || !err_dev) SPECA_FAIL(SPECA_EINVAL, "pred, truth and err_out must not be NULL");
+  if (tau_dev && !accept_dev) SPECA_FAIL(SPECA_EINVAL, "accept_out is NULL but tau_per_row is given");
+  if (n_rows < 1) SPECA_FAIL(SPECA_EINVAL, "n_rows = %d", n_rows);
+  if (E < 1) SPECA_FAIL(SPECA_EINVAL, "elems_per_row = %lld", static_cast<long long>(E));
+  if (dtype != SPECA_F32 && dtype != SPECA_BF16) SPECA_FAIL(SPECA_EINVAL, "dtype = %d", dtype);
+  if (!(eps >= 0.0f)) SPECA_FAIL(SPECA_EINVAL, "eps < 0");
+  const int64_t chunks = verify_chunks(E);
+  const int64_t per_launch = std::min<int64_t>(n_rows, kMaxRows) * chunks;
+  if (per_launch > SPECA_VERIFY_STATIC_MAX_PARTIALS)
+    SPECA_FAIL(SPECA_EINVAL, "speca_verify_static: %lld partial sums per launch (%d rows x %lld chunks) exceed the static scratch of %d",
+               static_cast<long long>(per_launch), std::min(n_rows, kMaxRows), static_cast<long long>(chunks), SPECA_VERIFY_STATIC_MAX_PARTIALS);
+  if (!ctx->static_partial) SPECA_FAIL(SPECA_ESTATE, "the static scratch was not resolved at create");
+  const int metric = ctx->cache_ready ? ctx->cfg.metric : SPECA_METRIC_L2;
+  const size_t esz = dtype_size(dtype);
+  // row groups of one call reuse the scratch one after the other: same stream, so in order
+  for (int r0 = 0; r0 < n_rows; r0 += kMaxRows) {
+    const int n = std::min(kMaxRows, n_rows - r0);
+    const char* p = static_cast<const char*>(pred) + static_cast<size_t>(r0) * E * esz;
+    const char* t = static_cast<const char*>(truth) + static_cast<size_t>(r0) * E * esz;
+    SPECA_TRY(launch_verify(metric, p, dtype, t, dtype, E, nullptr, nullptr, 0, n, eps, tau_dev ? tau_dev + r0 : nullptr, ctx->static_partial,
+                            err_dev + r0, accept_dev ? accept_dev + r0 : nullptr, ctx->stream));
+  }
+  return ok();
+}
+
 static Error labels_for_rows(const speca_ctx* ctx, const speca_cond* cond, std::vector<int32_t>* out) {
   out->assign(ctx->batch_rows, 0);
   if (ctx->desc.kind == SPECA_MODEL_DIT) {
@@ -446,6 +498,12 @@ int speca_verify(speca_ctx* ctx, const void* pred, const void* truth, int n_rows
                  const float* tau_per_row, float eps, float* err_out, uint8_t* accept_out) {
   if (!ctx) return SPECA_EINVAL;
   return finish(ctx, verify_impl(ctx, pred, truth, n_rows, elems_per_row, dtype, tau_per_row, eps, err_out, accept_out));
+}
+
+int speca_verify_static(speca_ctx* ctx, const void* pred, const void* truth, int n_rows, int64_t elems_per_row, int dtype,
+                        const float* tau_per_row, float eps, float* err_out, uint8_t* accept_out) {
+  if (!ctx) return SPECA_EINVAL;
+  return finish(ctx, verify_static_impl(ctx, pred, truth, n_rows, elems_per_row, dtype, tau_per_row, eps, err_out, accept_out));
 }
 
 int speca_spec_step(speca_ctx* ctx, const void* x, const speca_cond* cond, int step, const int32_t* rows, int n_rows,

@@ -53,6 +53,7 @@ struct speca_ctx {
   hipEvent_t lane_join[speca::kMaxLanes] = {};
 
   speca::VerifyScratch vs;
+  float* static_partial = nullptr;            // device address of the file-scope reduction scratch on this context's device
   float* model_out = nullptr;                 // [batch_rows][latent elems] fp32: model outputs of a trajectory's current step
   size_t model_out_cap = 0;                   // bytes
   std::unique_ptr<speca::Model> model;
