@@ -164,6 +164,23 @@ def compare_traces(tr, gtr, dtype):
     return compared, complete
 
 
+def all_decisive(tr, dtype):
+    """True if every verified decision of the oracle's trace lies outside the band in which compare_traces lets a
+    decision flip: then the device must reproduce the whole schedule, and the latents are compared."""
+    n = NOISE[dtype]
+    for b in range(tr.kind.shape[0]):
+        for s in range(tr.kind.shape[1]):
+            if not np.all(np.isnan(tr.err[b, s])):
+                e, tau = float(np.nanmax(tr.err[b, s])), float(tr.tau[s])
+                if not (e > tau * 1.02 + 1e-7 or np.sqrt(e * e + n * n) < tau * 0.98):
+                    return False
+    return True
+
+
+def must_complete(tr, dtype):
+    return dtype == "f32" or all_decisive(tr, dtype)
+
+
 def test_config1_trajectory(tiny):
     """Configuration 1: 20 DDIM steps, order 1, interval 4, verify = last block, tau 0.05 -> 0.01 linear."""
     s, w, om, ctx = tiny
@@ -173,7 +190,7 @@ def test_config1_trajectory(tiny):
     compared, complete = compare_traces(tr, gtr, s.dtype)
     print(f"decisions compared {compared}, schedules identical to the end: {complete}")
     assert compared >= 10
-    if s.dtype == "f32":
+    if must_complete(tr, s.dtype):
         assert complete
     if complete:
         assert max_abs_rel(got, exp) <= _tol(s)
@@ -189,10 +206,88 @@ def test_config1_geometric_and_newton(tiny):
         exp, tr, got, gtr = _run_both(s, om, ctx, 20, 2, kw, tau)
         compared, complete = compare_traces(tr, gtr, s.dtype)
         assert compared >= 6, kw
-        if s.dtype == "f32":
+        if must_complete(tr, s.dtype):
             assert complete, kw
         if complete:
             assert max_abs_rel(got, exp) <= _tol(s), kw
+
+
+def test_decisive_margins_force_latent_comparison(tiny):
+    """A trajectory whose every decision is far from the threshold in the oracle (>= 10 % after the bf16 noise
+    allowance): no flip is tolerated for either dtype, so schedule, counts, errors and final latents are all
+    compared.  Constant threshold 0.16, order 2, interval 5: 27 accepted and 12 rejected attempts over 3 samples;
+    both cache layouts, with and without guidance."""
+    s, w, om, ctx = tiny
+    S, B = 14, 3
+    tau = np.full(S, 0.16, np.float32)
+    for kw, scale in ((dict(order=2, interval=5), 0.0), (dict(order=2, interval=5, cache_layout="ring"), 1.5)):
+        exp, tr, got, gtr = _run_both(s, om, ctx, S, B, kw, tau, cfg_scale=scale, seed=3)
+        m = np.inf
+        for b in range(B):
+            for st in range(S):
+                if not np.all(np.isnan(tr.err[b, st])):
+                    e = float(np.nanmax(tr.err[b, st]))
+                    m = min(m, (e - 0.16) / 0.16 if e > 0.16 else (0.16 - np.sqrt(e * e + NOISE["bf16"] ** 2)) / 0.16)
+        assert m >= 0.10 and all_decisive(tr, "bf16"), m                # the case itself: decided by the oracle alone
+        assert (tr.kind == 1).sum() >= 20 and (tr.kind == 2).sum() >= 8
+        compared, complete = compare_traces(tr, gtr, s.dtype)
+        assert complete and compared == int((tr.kind != 0).sum()), (kw, compared)
+        assert np.array_equal(gtr["kind"], tr.kind), kw
+        assert gtr["n_full"] == tr.n_full and gtr["n_spec"] == int((tr.kind == 1).sum()) and gtr["n_reject"] == int((tr.kind == 2).sum())
+        assert max_abs_rel(got, exp) <= _tol(s), kw
+
+
+def test_other_metrics_through_the_sampler(tiny):
+    """The appendix's other error metrics chosen through speca_cfg.metric and used by speca_sample's verifier
+    (not only by the stand-alone reduction): one trajectory per metric against the oracle run with that metric."""
+    import paper_2509_11628_amd as sp
+    from paper_2509_11628_amd import binding as bd
+    s, w, om, ctx = tiny
+    S, B = 12, 2
+    ts, ab = si.ddim_tables(S)
+    lat = si.make_latents(B, s.in_channels, s.latent_hw, 3)
+    lab = si.make_labels(B, s.num_classes, 3)
+    sol = osamp.Solver("ddim", ts, ab, 0.0)
+    # thresholds per metric: cosine distance is about e^2 / 2 of the relative L2 error e, L-infinity is larger than L2
+    for name, code, tau0 in (("l1", bd.METRIC_L1, 0.16), ("linf", bd.METRIC_LINF, 0.3), ("cosine", bd.METRIC_COSINE, 0.012)):
+        tau = np.full(S, tau0, np.float32)
+        exp, tr = osamp.sample(om, osamp.SpecaConfig(order=2, interval=5, metric=name, cache_store="bf16" if s.dtype == "bf16" else None),
+                               sol, tau, lat, lab)
+        ctx.init_cache(sp.make_cfg(order=2, interval=5, metric=code), B)
+        xd = torch.from_numpy(lat).cuda()
+        gtr = ctx.sample(xd, ts, ab, tau, labels=lab)
+        print(f"\n[{s.dtype}] metric {name}: kinds {tr.kind.tolist()} errors {np.round(tr.err[..., 0], 4).tolist()}")
+        assert (tr.kind == 1).sum() > 0 and (tr.kind == 2).sum() > 0, name
+        if s.dtype == "f32":
+            assert np.array_equal(gtr["kind"], tr.kind), name
+            m = ~np.isnan(tr.err[..., 0])
+            np.testing.assert_allclose(gtr["err"][..., 0][m], tr.err[..., 0][m], rtol=2e-3, atol=1e-6, err_msg=name)
+            assert max_abs_rel(xd.cpu().numpy(), exp) <= 1e-5, name
+        else:
+            compared, complete = compare_traces_metric(tr, gtr, name)
+            assert compared >= 4, name
+            if complete:
+                assert max_abs_rel(xd.cpu().numpy(), exp) <= 2e-2, name
+
+
+def compare_traces_metric(tr, gtr, name):
+    """bf16 runs under another metric: the noise the device adds is metric-dependent (cosine distance is second
+    order in the rounding noise, L-infinity sees single elements), so a decision within 15 % of the threshold
+    may flip; from there on the sample is no longer compared."""
+    compared, complete = 0, True
+    for b in range(tr.kind.shape[0]):
+        for st in range(tr.kind.shape[1]):
+            ko, kg = int(tr.kind[b, st]), int(gtr["kind"][b, st])
+            e, tau = float(tr.err[b, st, 0]), float(tr.tau[st])
+            if ko != kg:
+                assert not np.isnan(e) and abs(e - tau) <= 0.15 * tau + 2e-3, (name, b, st, ko, kg, e, tau)
+                complete = False
+                break
+            if not np.isnan(e):
+                compared += 1
+                ge = float(gtr["err"][b, st, 0])
+                assert abs(ge - e) <= 0.15 * e + (3e-4 if name == "cosine" else 1.2e-2), (name, b, st, ge, e)
+    return compared, complete
 
 
 def test_threshold_zero_is_plain_sampling(tiny):
@@ -224,7 +319,7 @@ def test_guided_trajectory(tiny):
     print(f"\n[{s.dtype}] guided: min margin {_margin(tr):.3e}; kinds {tr.kind.tolist()}")
     compared, complete = compare_traces(tr, gtr, s.dtype)
     assert compared >= 6
-    if s.dtype == "f32":
+    if must_complete(tr, s.dtype):
         assert complete
     if complete:
         assert max_abs_rel(got, exp) <= _tol(s)
@@ -245,7 +340,7 @@ def test_ring_layout_trajectories(tiny):
         compared, complete = compare_traces(tr, gtr, s.dtype)
         print(f"\n[{s.dtype}] ring {kw}: kinds {tr.kind.tolist()} compared {compared} complete {complete}")
         assert compared >= 4, kw
-        if s.dtype == "f32":
+        if must_complete(tr, s.dtype):
             assert complete, kw
         if complete:
             assert max_abs_rel(got, exp) <= _tol(s), kw
@@ -267,7 +362,7 @@ def test_stochastic_solver_trajectory(tiny):
         compared, complete = compare_traces(tr, gtr, s.dtype)
         print(f"\n[{s.dtype}] ancestral: kinds {tr.kind.tolist()} compared {compared} complete {complete}")
         assert compared >= 4
-        if s.dtype == "f32":
+        if must_complete(tr, s.dtype):
             assert complete
         if complete:
             assert max_abs_rel(got, exp) <= _tol(s)
@@ -399,4 +494,51 @@ def test_config3_full_size_sampled():
         compared, complete = compare_traces(tr, {"kind": gtr["kind"][:1], "err": gtr["err"][:1]}, "bf16")
         assert compared == 3 and complete, layout
         assert max_abs_rel(finals[0][:1], exp1) <= 2e-2, layout
+    ctx.close()
+
+
+def test_config3_full_size_diverging_schedules():
+    """Configuration 3 at full size with samples whose schedules diverge, so that every step after the first splits
+    the batch into a speculative row list and a full row list (rejected rows recomputed at M = 2048 while the other
+    half of the batch finishes from forecasts): 8 samples x guidance pair, bf16, 4 lanes, ring layout, 5 DDIM steps.
+    With seeded random weights the verification errors of equally scaled latents lie within 2 % of each other, so the
+    latents are scaled per sample (0.4 .. 0.7 and 1.4 .. 2.0): the error grows with the scale and per-step thresholds
+    placed in the gap send the two groups opposite ways at every step.  One sample of each group is checked against
+    the oracle run on that sample alone (samples are independent): schedule, errors, final latents."""
+    import paper_2509_11628_amd as sp
+    from paper_2509_11628_amd import binding as bd
+    s = si.dit_xl2("bf16")
+    w = si.make_dit_weights(s, 0)
+    ctx = sp.Context(sp.dit_desc(s), sp.to_device(w, bd.BF16))
+    B, S = 8, 5
+    scales = np.array([0.4, 0.5, 0.6, 0.7, 1.4, 1.6, 1.8, 2.0], np.float32)
+    lat = si.make_latents(B, s.in_channels, s.latent_hw, 0) * scales[:, None, None, None]
+    lab = si.make_labels(B, s.num_classes, 0)
+    ts, ab = si.ddim_tables(S)
+    tau = np.array([0.0, 0.5, 0.65, 0.55, 0.5], np.float32)
+    ctx.set_lanes(4)
+    ctx.init_cache(sp.make_cfg(order=2, interval=5, layout=bd.CACHE_RING), 2 * B)
+    x = torch.from_numpy(lat).cuda()
+    gtr = ctx.sample(x, ts, ab, tau, cfg_scale=1.5, labels=lab)
+    got = x.cpu().numpy()
+    print(f"\nkinds {gtr['kind'].tolist()}\nerrors {np.round(np.nanmax(gtr['err'], axis=2), 4).tolist()}")
+    # the two groups go opposite ways at every step: each launch after step 0 holds half of the batch
+    assert gtr["kind"][:4].tolist() == [[0, 1, 2, 1, 2]] * 4 and gtr["kind"][4:].tolist() == [[0, 2, 1, 2, 1]] * 4
+    assert gtr["n_spec"] == 16 and gtr["n_reject"] == 16 and gtr["n_full"] == 24
+    om = odit.DiTOracle(s, w)
+    sol = osamp.Solver("ddim", ts, ab, 1.5)
+    for b in (1, 6):
+        exp1, tr = osamp.sample(om, osamp.SpecaConfig(order=2, interval=5, cache_store="bf16", cache_layout="ring"), sol, tau,
+                                lat[b:b + 1], lab[b:b + 1])
+        print(f"sample {b}: oracle kinds {tr.kind[0].tolist()} errors {np.round(np.nanmax(tr.err[0], axis=1), 4).tolist()}")
+        assert all_decisive(tr, "bf16"), b                              # the thresholds sit in the gap for the oracle too
+        compared, complete = compare_traces(tr, {"kind": gtr["kind"][b:b + 1], "err": gtr["err"][b:b + 1]}, "bf16")
+        assert compared == 4 and complete, b
+        assert max_abs_rel(got[b:b + 1], exp1) <= 2e-2, b
+    # the same trajectory run serially gives the same bits
+    ctx.set_lanes(1)
+    ctx.init_cache(sp.make_cfg(order=2, interval=5, layout=bd.CACHE_RING), 2 * B)
+    x1 = torch.from_numpy(lat).cuda()
+    ctx.sample(x1, ts, ab, tau, cfg_scale=1.5, labels=lab)
+    assert np.array_equal(x1.cpu().numpy(), got)
     ctx.close()

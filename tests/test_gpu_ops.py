@@ -45,6 +45,8 @@ SHAPES = [  # M, N, K
     # one and two K-steps (the rings re-read the last tile into a free stage past the end of K): 3-stage and 2-stage
     # 256x128, and the shortest K the 256x256 tile takes
     (4096, 3456, 64), (4000, 1160, 64), (4096, 3456, 128), (4608, 3072, 2048),
+    # the MLP GEMMs of configuration 3 at full size
+    (4096, 4608, 1152), (4096, 1152, 4608),
 ]
 
 
@@ -52,8 +54,11 @@ SHAPES = [  # M, N, K
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("act", [0, 1, 2])
 def test_linear(M, N, K, dtype, act):
-    if act and (M, N, K) not in ((200, 192, 72), (130, 1152, 1152)):
-        pytest.skip("activations checked on two shapes")
+    # activations: two register-staged shapes and, for the direct-to-LDS loop, one 256x128 tile (2- and 3-stage ring),
+    # one 256x256 tile and the fc1 shape of configuration 3 (one wave of 256x256 tiles plus a remainder launch)
+    if act and (M, N, K) not in ((200, 192, 72), (130, 1152, 1152), (4000, 1160, 256), (4000, 3400, 2048), (4096, 3456, 128),
+                                 (4096, 4608, 1152)):
+        return
     bd = _bd()
     rng = np.random.default_rng(M * 7 + N * 3 + K)
     a = si._store(rng.standard_normal((M, K)).astype(np.float32), dtype)
@@ -101,6 +106,55 @@ def test_attention(rows, T, H, hd, dtype):
     scale = np.max(np.abs(exp))
     # bf16: probabilities and the output are rounded to bf16 on the device (2^-9 relative each)
     assert np.max(np.abs(got - exp)) <= (2e-5 if dtype == "f32" else 1.2e-2) * scale
+
+
+@pytest.mark.parametrize("M,N,K,act", [(27286, 3072, 3072, 0), (27286, 12288, 3072, 1), (4608, 3072, 12288, 0), (4608, 15360 // 5 * 3, 3072, 0)])
+def test_linear_at_mmdit_sizes_sampled_rows(M, N, K, act):
+    """The linear layers at the row counts of configurations 4 and 5 (4608 / 27286 tokens, hidden 3072, MLP 12288):
+    the device computes the whole product, the oracle a sample of its rows (first and last tile, ragged tail
+    included) by the plain definition."""
+    bd = _bd()
+    g = torch.Generator(device="cuda").manual_seed(M + N + K)
+    a = torch.randn((M, K), generator=g, device="cuda").to(torch.bfloat16)
+    w = (torch.randn((N, K), generator=g, device="cuda") * 0.03).to(torch.bfloat16)
+    b = (torch.randn((N,), generator=g, device="cuda") * 0.1).to(torch.bfloat16)
+    out = bd.linear(a, w, b, act)
+    rng = np.random.default_rng(M)
+    rows = np.unique(np.concatenate([np.arange(0, 8), np.arange(M - 40, M), rng.integers(0, M, 80)]))
+    ridx = torch.from_numpy(rows).cuda()
+    exp = odit.linear(a[ridx].float().cpu().numpy().astype(np.float64), w.float().cpu().numpy().astype(np.float64),
+                      b.float().cpu().numpy().astype(np.float64))
+    if act == 1:
+        exp = odit.gelu_tanh(exp)
+    _check(out[ridx], exp, "bf16", K)
+
+
+@pytest.mark.parametrize("T,H", [(4608, 2), (27286, 1)])
+def test_attention_at_mmdit_lengths_sampled_queries(T, H):
+    """Attention at the sequence lengths of configurations 4 (4096 + 512 tokens) and 5 (27030 + 256), head_dim 128:
+    the device computes every query; the oracle's plain softmax over ALL keys is evaluated for a few hundred sampled
+    query rows (first tile, ragged last tile, random ones).  Keys are given a per-key offset along one direction so
+    that the scores are far from uniform and the running maximum really moves along the hundreds of key tiles."""
+    bd = _bd()
+    hd = 128
+    g = torch.Generator(device="cuda").manual_seed(T)
+    qkv = torch.randn((1, T, 3, H, hd), generator=g, device="cuda")
+    qkv[:, :, 1, :, 0] += torch.linspace(-3.0, 3.0, T, device="cuda")[None, :, None]        # keys drift along dim 0
+    qkv[:, :, 0, :, 0] += 2.0                                                                 # every query looks along it
+    qkv[:, :, 0] *= 2.5                                                                       # peaked softmax (score std 2.5)
+    qkv[:, :, 2, :, 1] += torch.linspace(-2.0, 2.0, T, device="cuda")[None, :, None]        # values say which keys were attended
+    qkv = qkv.to(torch.bfloat16)
+    out = bd.attention(qkv.reshape(1, T, 3 * H * hd).contiguous(), H)
+    rng = np.random.default_rng(T)
+    qs = np.unique(np.concatenate([np.arange(0, 70), np.arange(T - 150, T), rng.integers(0, T, 160)]))
+    host = qkv.float().cpu().numpy().astype(np.float64)
+    q = host[:, qs, 0].transpose(0, 2, 1, 3)                       # [1, H, nq, hd]
+    k = host[:, :, 1].transpose(0, 2, 1, 3)                        # [1, H, T, hd]
+    v = host[:, :, 2].transpose(0, 2, 1, 3)
+    exp = odit.attention(q, k, v).transpose(0, 2, 1, 3).reshape(len(qs), H * hd)
+    got = out[0, torch.from_numpy(qs).cuda()].float().cpu().numpy().astype(np.float64)
+    scale = np.max(np.abs(exp))
+    assert np.max(np.abs(got - exp)) <= 1.2e-2 * scale, float(np.max(np.abs(got - exp)) / scale)
 
 
 def test_linear_rejects_bad_arguments():
