@@ -198,12 +198,12 @@ static Error create_impl(speca_ctx** out, const speca_model_desc* desc, const sp
     if (v >= 1 && v <= kMaxLanes) ctx->lanes = v;
   }
   VerifyScratch& v = ctx->vs;
-  SPECA_HIP(hipMalloc(&v.tau_dev, kMaxRows * sizeof(float)));
-  SPECA_HIP(hipMalloc(&v.err_dev, kMaxRows * sizeof(float)));
-  SPECA_HIP(hipMalloc(&v.acc_dev, kMaxRows));
-  SPECA_HIP(hipHostMalloc(&v.h_tau, kMaxRows * sizeof(float), hipHostMallocDefault));
-  SPECA_HIP(hipHostMalloc(&v.h_err, kMaxRows * sizeof(float), hipHostMallocDefault));
-  SPECA_HIP(hipHostMalloc(&v.h_acc, kMaxRows, hipHostMallocDefault));
+  SPECA_HIP(hipMalloc(&v.tau_dev, kMaxVerifyRows * sizeof(float)));
+  SPECA_HIP(hipMalloc(&v.err_dev, kMaxVerifyRows * sizeof(float)));
+  SPECA_HIP(hipMalloc(&v.acc_dev, kMaxVerifyRows));
+  SPECA_HIP(hipHostMalloc(&v.h_tau, kMaxVerifyRows * sizeof(float), hipHostMallocDefault));
+  SPECA_HIP(hipHostMalloc(&v.h_err, kMaxVerifyRows * sizeof(float), hipHostMallocDefault));
+  SPECA_HIP(hipHostMalloc(&v.h_acc, kMaxVerifyRows, hipHostMallocDefault));
   *out = ctx.release();
   return ok();
 }
@@ -342,8 +342,8 @@ static Error verify_impl(speca_ctx* ctx, const void* pred, const void* truth, in
   const int metric = ctx->cache_ready ? ctx->cfg.metric : SPECA_METRIC_L2;
   const size_t esz = dtype_size(dtype);
   VerifyScratch& v = ctx->vs;
-  for (int r0 = 0; r0 < n_rows; r0 += kMaxRows) {
-    const int n = std::min(kMaxRows, n_rows - r0);
+  for (int r0 = 0; r0 < n_rows; r0 += kMaxVerifyRows) {
+    const int n = std::min(kMaxVerifyRows, n_rows - r0);
     SPECA_TRY(ensure_partial(ctx, static_cast<size_t>(n) * verify_chunks(E) * 3));
     if (tau) {
       std::memcpy(v.h_tau, tau + r0, n * sizeof(float));

@@ -249,7 +249,7 @@ __global__ __launch_bounds__(kThreads) void verify_partial_kernel(const T* __res
   if (VEC) {
     // T and TT may differ in width: walk in units of 8 elements
     constexpr int V = 8;
-    for (int64_t e = begin + static_cast<int64_t>(threadIdx.x) * V; e < end; e += kThreads * V) {
+    auto one = [&](int64_t e) {
       float tv[V], pv[V];
       if (sizeof(TT) == 2) {
         Vec<bf16_t>::unpack(*reinterpret_cast<const uint4*>(t + e), tv);
@@ -274,6 +274,13 @@ __global__ __launch_bounds__(kThreads) void verify_partial_kernel(const T* __res
         }
 #pragma unroll
       for (int q = 0; q < V; ++q) acc_update<METRIC>(pv[q], tv[q], a0, a1, a2);
+    };
+    if (end - begin == kChunk) {
+      // a whole chunk: fixed trip count, so the loads of all trips are in flight before the first sum (same order of sums)
+#pragma unroll
+      for (int it = 0; it < kChunk / (kThreads * V); ++it) one(begin + (static_cast<int64_t>(it) * kThreads + threadIdx.x) * V);
+    } else {
+      for (int64_t e = begin + static_cast<int64_t>(threadIdx.x) * V; e < end; e += kThreads * V) one(e);
     }
   } else {
     for (int64_t e = begin + threadIdx.x; e < end; e += kThreads) {
@@ -492,7 +499,8 @@ static Error launch_verify_m(const void* pred, int pred_dtype, const void* truth
 Error launch_verify(int metric, const void* pred, int pred_dtype, const void* truth, int truth_dtype, int64_t E,
                     const CacheGeom* g, const RowTable* rt, int slot, int n_rows, float eps, const float* tau_dev,
                     float* partial, float* err_dev, uint8_t* accept_dev, hipStream_t st) {
-  if (n_rows <= 0 || n_rows > kMaxRows) SPECA_FAIL(SPECA_EINVAL, "verify: %d rows in one launch", n_rows);
+  // the cache form takes its rows from a row table; two tensors can be reduced for more rows at once
+  if (n_rows <= 0 || n_rows > (g ? kMaxRows : kMaxVerifyRows)) SPECA_FAIL(SPECA_EINVAL, "verify: %d rows in one launch", n_rows);
   if (E <= 0) SPECA_FAIL(SPECA_EINVAL, "verify: elems_per_row = %lld", static_cast<long long>(E));
   switch (metric) {
     case SPECA_METRIC_L2: return launch_verify_m<SPECA_METRIC_L2>(pred, pred_dtype, truth, truth_dtype, E, g, rt, slot, n_rows, eps, tau_dev, partial, err_dev, accept_dev, st);

@@ -17,14 +17,14 @@ struct Model;
 // Small pinned host area + device mirrors for the per-launch scalars that travel each
 // speculative step (thresholds in; errors and verdicts out).
 struct VerifyScratch {
-  float* tau_dev = nullptr;        // [kMaxRows]
-  float* err_dev = nullptr;        // [kMaxRows]
-  uint8_t* acc_dev = nullptr;      // [kMaxRows]
+  float* tau_dev = nullptr;        // [kMaxVerifyRows]
+  float* err_dev = nullptr;        // [kMaxVerifyRows]
+  uint8_t* acc_dev = nullptr;      // [kMaxVerifyRows]
   float* partial = nullptr;        // [rows][chunks][3]
   size_t partial_cap = 0;          // floats
-  float* h_tau = nullptr;          // pinned [kMaxRows]
-  float* h_err = nullptr;          // pinned [kMaxRows]
-  uint8_t* h_acc = nullptr;        // pinned [kMaxRows]
+  float* h_tau = nullptr;          // pinned [kMaxVerifyRows]
+  float* h_err = nullptr;          // pinned [kMaxVerifyRows]
+  uint8_t* h_acc = nullptr;        // pinned [kMaxVerifyRows]
 };
 
 }  // namespace speca

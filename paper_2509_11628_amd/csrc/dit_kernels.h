@@ -25,6 +25,10 @@ Error launch_ln_modulate2(int dtype, const float* h, const float* shift, const f
 // gate_off_dev: int32[2 * n_slots], entry 2j for elements below split_elem, 2j+1 from there on.
 Error launch_forecast_fold(const CacheGeom& g, const RowTable& rt, const float* h_in, float* h_out, const float* mod,
                            int64_t mod_stride, const int32_t* gate_off_dev, int64_t split_elem, int s0, int s1, int D, hipStream_t st);
+// One pass for both hidden states of a speculative attempt: h_mid = h_in + slots [s0, s_mid), h_out = h_in + slots [s0, s1);
+// s0 <= s_mid < s1 (s_mid == s0: h_mid = h_in).  h_in may be h_mid (in place).
+Error launch_forecast_fold2(const CacheGeom& g, const RowTable& rt, const float* h_in, float* h_mid, int s_mid, float* h_out, const float* mod,
+                            int64_t mod_stride, const int32_t* gate_off_dev, int64_t split_elem, int s0, int s1, int D, hipStream_t st);
 Error launch_unpatchify(const float* tok, const RowLabels& rows, float* out, int n, int C, int Hh, int Ww, int p, hipStream_t st);
 
 }  // namespace speca

@@ -168,11 +168,13 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // Speculative step: h_out[i][e] = h_in[i][e] + sum_{slot in [s0,s1)} gate_slot[i][d] * sum_o c[i][o] D^o[slot][row_i][e]
 // (Eq. 2 for every slot, folded into the residual stream; only the hidden state is written).
+// With h_mid != nullptr the running sum after slots [s0, s_mid) is written there as well: the hidden state that
+// enters the verify block and the one the accepted path finishes from come out of one pass over the cache.
 // gate of slot j for compact row i: mod[i * mod_stride + gate_off[2j + s] + d], s = 0 for elements below
 // split_elem (the text tokens of a two-stream block), 1 from there on.
 template <typename T, int NT>
 __global__ __launch_bounds__(256) void forecast_fold_kernel(CacheGeom g, RowTable rt, const float* h_in,   // h_in may be h_out (in place)
-                                                            float* h_out, const float* __restrict__ mod,
+                                                            float* h_out, float* h_mid, int s_mid, const float* __restrict__ mod,
                                                             int64_t mod_stride, const int32_t* __restrict__ gate_off, int64_t split_elem,
                                                             int s0, int s1, int D) {
   constexpr int V = 8;     // 8 elements per thread: 2 x 16 B of fp32 hidden, 16 B (bf16) or 2 x 16 B (fp32) of every cached tensor
@@ -198,32 +200,43 @@ __global__ __launch_bounds__(256) void forecast_fold_kernel(CacheGeom g, RowTabl
   const float* mrow = mod + static_cast<int64_t>(i) * mod_stride + d;
   const bool sel = e >= split_elem;
   // four slots per trip: 4 * NT cache loads in flight per lane (measured best among 1/2/4/8)
+  auto fold = [&](int sa, int sb) {
 #pragma unroll 4
-  for (int slot = s0; slot < s1; ++slot) {
-    const int off0 = gate_off[2 * slot], off1 = gate_off[2 * slot + 1];     // block-uniform: scalar loads
-    const float* gp = mrow + (sel ? off1 : off0);
-    const float4 g0 = *reinterpret_cast<const float4*>(gp), g1 = *reinterpret_cast<const float4*>(gp + 4);
-    const float gg[V] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
-    float f[V];
+    for (int slot = sa; slot < sb; ++slot) {
+      const int off0 = gate_off[2 * slot], off1 = gate_off[2 * slot + 1];     // block-uniform: scalar loads
+      const float* gp = mrow + (sel ? off1 : off0);
+      const float4 g0 = *reinterpret_cast<const float4*>(gp), g1 = *reinterpret_cast<const float4*>(gp + 4);
+      const float gg[V] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+      float f[V];
 #pragma unroll
-    for (int q = 0; q < V; ++q) f[q] = 0.0f;
+      for (int q = 0; q < V; ++q) f[q] = 0.0f;
 #pragma unroll
-    for (int o = 0; o < NT; ++o) {
-      float t8[V];
-      const T* p = base + g.offset(slot, oc[o], row) + e;
-      if (sizeof(T) == 2) {
-        const u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));     // read once per step: keep it out of the caches' way
+      for (int o = 0; o < NT; ++o) {
+        float t8[V];
+        const T* p = base + g.offset(slot, oc[o], row) + e;
+        if (sizeof(T) == 2) {
+          const u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));     // read once per step: keep it out of the caches' way
 #pragma unroll
-        for (int q = 0; q < 4; ++q) { t8[2 * q] = __uint_as_float(r[q] << 16); t8[2 * q + 1] = __uint_as_float(r[q] & 0xFFFF0000u); }
-      } else {
-        const float4 r0 = *reinterpret_cast<const float4*>(p), r1 = *reinterpret_cast<const float4*>(p + 4);
-        t8[0] = r0.x; t8[1] = r0.y; t8[2] = r0.z; t8[3] = r0.w; t8[4] = r1.x; t8[5] = r1.y; t8[6] = r1.z; t8[7] = r1.w;
+          for (int q = 0; q < 4; ++q) { t8[2 * q] = __uint_as_float(r[q] << 16); t8[2 * q + 1] = __uint_as_float(r[q] & 0xFFFF0000u); }
+        } else {
+          const float4 r0 = *reinterpret_cast<const float4*>(p), r1 = *reinterpret_cast<const float4*>(p + 4);
+          t8[0] = r0.x; t8[1] = r0.y; t8[2] = r0.z; t8[3] = r0.w; t8[4] = r1.x; t8[5] = r1.y; t8[6] = r1.z; t8[7] = r1.w;
+        }
+#pragma unroll
+        for (int q = 0; q < V; ++q) f[q] = fmaf(c[o], t8[q], f[q]);
       }
 #pragma unroll
-      for (int q = 0; q < V; ++q) f[q] = fmaf(c[o], t8[q], f[q]);
+      for (int q = 0; q < V; ++q) acc[q] = fmaf(gg[q], f[q], acc[q]);
     }
-#pragma unroll
-    for (int q = 0; q < V; ++q) acc[q] = fmaf(gg[q], f[q], acc[q]);
+  };
+  if (h_mid) {                                                                // block-uniform
+    fold(s0, s_mid);
+    float* mp = h_mid + static_cast<int64_t>(i) * g.E + e;
+    *reinterpret_cast<float4*>(mp) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    *reinterpret_cast<float4*>(mp + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    fold(s_mid, s1);
+  } else {
+    fold(s0, s1);
   }
   float* op = h_out + static_cast<int64_t>(i) * g.E + e;
   *reinterpret_cast<float4*>(op) = make_float4(acc[0], acc[1], acc[2], acc[3]);
@@ -308,31 +321,43 @@ Error launch_ln_modulate2(int dtype, const float* h, const float* shift, const f
                              : ln_mod_t<float>(h, shift, scale, shift2, scale2, split_tok, mod_stride, y, n_tokens, tokens_per_row, D, st);
 }
 
-template <typename T>
-static Error fold_t(const CacheGeom& g, const RowTable& rt, const float* h_in, float* h_out, const float* mod, int64_t mod_stride,
-                    const int32_t* gate_off, int64_t split_elem, int s0, int s1, int D, hipStream_t st) {
-  int mo = 0;
-  for (int i = 0; i < rt.n; ++i) mo = rt.order[i] > mo ? rt.order[i] : mo;
-  dim3 grid(blocks_for(g.E, 256 * 8), rt.n);
-  switch (mo) {
-    case 0: forecast_fold_kernel<T, 1><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, split_elem, s0, s1, D); break;
-    case 1: forecast_fold_kernel<T, 2><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, split_elem, s0, s1, D); break;
-    case 2: forecast_fold_kernel<T, 3><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, split_elem, s0, s1, D); break;
-    case 3: forecast_fold_kernel<T, 4><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, split_elem, s0, s1, D); break;
-    default: forecast_fold_kernel<T, 5><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, mod, mod_stride, gate_off, split_elem, s0, s1, D); break;
-  }
+template <typename T, int NT>
+static Error fold_launch(const CacheGeom& g, const RowTable& rt, const float* h_in, float* h_out, float* h_mid, int s_mid, const float* mod,
+                         int64_t mod_stride, const int32_t* gate_off, int64_t split_elem, int s0, int s1, int D, hipStream_t st) {
+  const dim3 grid(blocks_for(g.E, 256 * 8), rt.n);
+  forecast_fold_kernel<T, NT><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, h_mid, s_mid, mod, mod_stride, gate_off, split_elem, s0, s1, D);
   SPECA_HIP(hipGetLastError());
   return ok();
 }
 
+template <typename T>
+static Error fold_t(const CacheGeom& g, const RowTable& rt, const float* h_in, float* h_out, float* h_mid, int s_mid, const float* mod,
+                    int64_t mod_stride, const int32_t* gate_off, int64_t split_elem, int s0, int s1, int D, hipStream_t st) {
+  int mo = 0;
+  for (int i = 0; i < rt.n; ++i) mo = rt.order[i] > mo ? rt.order[i] : mo;
+  switch (mo) {
+    case 0: return fold_launch<T, 1>(g, rt, h_in, h_out, h_mid, s_mid, mod, mod_stride, gate_off, split_elem, s0, s1, D, st);
+    case 1: return fold_launch<T, 2>(g, rt, h_in, h_out, h_mid, s_mid, mod, mod_stride, gate_off, split_elem, s0, s1, D, st);
+    case 2: return fold_launch<T, 3>(g, rt, h_in, h_out, h_mid, s_mid, mod, mod_stride, gate_off, split_elem, s0, s1, D, st);
+    case 3: return fold_launch<T, 4>(g, rt, h_in, h_out, h_mid, s_mid, mod, mod_stride, gate_off, split_elem, s0, s1, D, st);
+    default: return fold_launch<T, 5>(g, rt, h_in, h_out, h_mid, s_mid, mod, mod_stride, gate_off, split_elem, s0, s1, D, st);
+  }
+}
+
 Error launch_forecast_fold(const CacheGeom& g, const RowTable& rt, const float* h_in, float* h_out, const float* mod,
                            int64_t mod_stride, const int32_t* gate_off_dev, int64_t split_elem, int s0, int s1, int D, hipStream_t st) {
+  return launch_forecast_fold2(g, rt, h_in, nullptr, s0, h_out, mod, mod_stride, gate_off_dev, split_elem, s0, s1, D, st);
+}
+
+Error launch_forecast_fold2(const CacheGeom& g, const RowTable& rt, const float* h_in, float* h_mid, int s_mid, float* h_out, const float* mod,
+                            int64_t mod_stride, const int32_t* gate_off_dev, int64_t split_elem, int s0, int s1, int D, hipStream_t st) {
   if (rt.n <= 0 || rt.n > kMaxRows) SPECA_FAIL(SPECA_EINVAL, "forecast_fold: %d rows", rt.n);
+  if (h_mid && (s_mid < s0 || s_mid >= s1)) SPECA_FAIL(SPECA_EINVAL, "forecast_fold: intermediate state after slot %d of [%d,%d)", s_mid, s0, s1);
   if (g.E % 8 || D % 8) SPECA_FAIL(SPECA_EUNSUPPORTED, "forecast_fold needs hidden %% 8 == 0");
   if (s0 < 0 || s1 > g.n_slots || s0 > s1) SPECA_FAIL(SPECA_EINVAL, "forecast_fold: slots [%d,%d)", s0, s1);
   if (split_elem < 0 || split_elem % 8) SPECA_FAIL(SPECA_EINVAL, "forecast_fold: split");
-  return g.dtype == SPECA_BF16 ? fold_t<bf16_t>(g, rt, h_in, h_out, mod, mod_stride, gate_off_dev, split_elem, s0, s1, D, st)
-                               : fold_t<float>(g, rt, h_in, h_out, mod, mod_stride, gate_off_dev, split_elem, s0, s1, D, st);
+  return g.dtype == SPECA_BF16 ? fold_t<bf16_t>(g, rt, h_in, h_out, h_mid, s_mid, mod, mod_stride, gate_off_dev, split_elem, s0, s1, D, st)
+                               : fold_t<float>(g, rt, h_in, h_out, h_mid, s_mid, mod, mod_stride, gate_off_dev, split_elem, s0, s1, D, st);
 }
 
 Error launch_unpatchify(const float* tok, const RowLabels& rows, float* out, int n, int C, int Hh, int Ww, int p, hipStream_t st) {

@@ -172,7 +172,7 @@ struct DiT final : Model {
   struct Lane {
     hipStream_t st;
     int o;
-    int shared = 0;     // other lanes run beside this one
+    int shared = 0;     // lanes that run side by side (0: this one alone)
   };
   const float* mod_at(int l, int which, int o = 0) const {
     return mod + static_cast<int64_t>(o) * mod_n + static_cast<int64_t>(l) * 6 * D + static_cast<int64_t>(which) * D;
@@ -197,7 +197,7 @@ struct DiT final : Model {
       SPECA_TRY(launch_ln_modulate(d.dtype, hl, mod_at(l, 0, ln.o), mod_at(l, 1, ln.o), mod_n, xn_l, M, T, D, st));
     }
     GemmEpi e;
-    e.mode = EPI_STORE; e.bias = blk[l].qkv_b; e.out = qkv_l; e.ldo = 3 * D;
+    e.mode = EPI_STORE; e.bias = blk[l].qkv_b; e.out = qkv_l; e.ldo = 3 * D; e.shared_chip = ln.shared;
     {
       ProfScope ps(ctx, st, SPECA_PROF_GEMM, 2.0 * Md * 3 * D * D, (Md * 4 * D + 3.0 * D * D) * esz);
       SPECA_TRY(launch_gemm(d.dtype, xn_l, D, blk[l].qkv_w, D, static_cast<int>(M), 3 * D, D, e, st));
@@ -211,6 +211,7 @@ struct DiT final : Model {
       SPECA_TRY(launch_attention(d.dtype, qkv_l, att_l, D, n, T, H, hd, st));
     }
     GemmEpi b;
+    b.shared_chip = ln.shared;
     b.mode = EPI_BRANCH; b.bias = blk[l].proj_b; b.h = hl; b.ldh = D; b.gate = mod_at(l, 2, ln.o); b.gate_stride = mod_n; b.tokens = T;
     if (refresh_rt) { b.refresh = 1; b.slot = 2 * l; b.g = ctx->geom; b.rt = *refresh_rt; }
     ProfScope ps(ctx, st, SPECA_PROF_GEMM, 2.0 * Md * D * D, (Md * D + 1.0 * D * D) * esz + Md * D * 8);
@@ -237,7 +238,7 @@ struct DiT final : Model {
       SPECA_TRY(launch_cache_warm(ctx->geom, *refresh_rt, 2 * l + 1, st));
     }
     GemmEpi e;
-    e.mode = EPI_GELU; e.bias = blk[l].fc1_b; e.out = f1_l; e.ldo = Dm;
+    e.mode = EPI_GELU; e.bias = blk[l].fc1_b; e.out = f1_l; e.ldo = Dm; e.shared_chip = ln.shared;
     {
       ProfScope ps(ctx, st, SPECA_PROF_GEMM, 2.0 * Md * Dm * D, (Md * (D + Dm) + 1.0 * D * Dm) * esz);
       SPECA_TRY(launch_gemm(d.dtype, xn_l, D, blk[l].fc1_w, D, static_cast<int>(M), Dm, D, e, st));
@@ -259,7 +260,12 @@ struct DiT final : Model {
   // Blocks [l0, l1) for all n rows, the row groups of the split side by side (launches interleaved
   // block by block so the lanes stay in step).  refresh_rt / truth as in the branch functions.
   Error run_blocks(speca_ctx* ctx, int l0, int l1, float* hs, int n, const RowTable* refresh_rt, float* truth_last_mlp) {
-    const LaneSplit ls = split_lanes(ctx, n, 2);
+    // Row groups side by side pay off for whole batches: 16 rows in four groups of four run a reference step 7 % faster
+    // than serially.  Eight rows (half a batch recomputed after rejections) are faster as one launch sequence whose tiles
+    // are chosen for the whole chip (+7 % on a trajectory of split steps), and the single verify block of a
+    // speculative attempt is best in two groups (+1 %).
+    const int min_rows = n <= 8 ? n + 1 : (l1 - l0 == 1 ? 8 : 4);
+    const LaneSplit ls = split_lanes(ctx, n, min_rows);
     RowTable sub[kMaxLanes];
     if (refresh_rt)
       for (int k = 0; k < ls.n_lanes; ++k) sub[k] = slice_table(*refresh_rt, ls.first[k], ls.first[k + 1] - ls.first[k]);
@@ -267,11 +273,11 @@ struct DiT final : Model {
     Error body = [&]() -> Error {
       for (int l = l0; l < l1; ++l) {
         for (int k = 0; k < ls.n_lanes; ++k) {
-          const Lane ln{ctx->lane_stream[k], ls.first[k], ls.n_lanes > 1 ? 1 : 0};
+          const Lane ln{ctx->lane_stream[k], ls.first[k], ls.n_lanes > 1 ? ls.n_lanes : 0};
           SPECA_TRY(attn_branch(ctx, ln, l, hs, ls.first[k + 1] - ls.first[k], refresh_rt ? &sub[k] : nullptr));
         }
         for (int k = 0; k < ls.n_lanes; ++k) {
-          const Lane ln{ctx->lane_stream[k], ls.first[k], ls.n_lanes > 1 ? 1 : 0};
+          const Lane ln{ctx->lane_stream[k], ls.first[k], ls.n_lanes > 1 ? ls.n_lanes : 0};
           SPECA_TRY(mlp_branch(ctx, ln, l, hs, ls.first[k + 1] - ls.first[k], refresh_rt ? &sub[k] : nullptr,
                                l == l1 - 1 ? truth_last_mlp : nullptr));
         }
@@ -332,12 +338,18 @@ struct DiT final : Model {
     SPECA_TRY(embed(ctx, x, x_mod, rows, n));
     // Eq. 2 for every slot before the verify block, folded into h
     const double tens = table_tensors(rt), Ed = static_cast<double>(ctx->geom.E);
-    {
-      ProfScope ps(ctx, SPECA_PROF_FORECAST, 0.0, 2.0 * lv * tens * Ed * esz + 2.0 * n * Ed * 4);
-      SPECA_TRY(launch_forecast_fold(ctx->geom, rt, h, h, mod, mod_n, gate_off_dev, 0, 0, 2 * lv, D, st));
-    }
-    // accepted path: forecasts for the verify block and everything after it -> h2
-    {
+    // and the accepted path's forecasts for the verify block and everything after it -> h2.  One pass over the cache
+    // when the verify block sits in the last quarter of the stack (the verify block then waits for a few more slots
+    // but the hidden state is read once and there is one launch); two passes otherwise, so that an early verify
+    // block does not wait for the whole cache.
+    if (4 * lv >= 3 * L) {
+      ProfScope ps(ctx, SPECA_PROF_FORECAST, 0.0, 2.0 * L * tens * Ed * esz + 3.0 * n * Ed * 4);
+      SPECA_TRY(launch_forecast_fold2(ctx->geom, rt, h, h, 2 * lv, h2, mod, mod_n, gate_off_dev, 0, 0, 2 * L, D, st));
+    } else {
+      {
+        ProfScope ps(ctx, SPECA_PROF_FORECAST, 0.0, 2.0 * lv * tens * Ed * esz + 2.0 * n * Ed * 4);
+        SPECA_TRY(launch_forecast_fold(ctx->geom, rt, h, h, mod, mod_n, gate_off_dev, 0, 0, 2 * lv, D, st));
+      }
       ProfScope ps(ctx, SPECA_PROF_FORECAST, 0.0, 2.0 * (L - lv) * tens * Ed * esz + 2.0 * n * Ed * 4);
       SPECA_TRY(launch_forecast_fold(ctx->geom, rt, h, h2, mod, mod_n, gate_off_dev, 0, 2 * lv, 2 * L, D, st));
     }

@@ -22,8 +22,8 @@ struct GemmEpi {
   const void* bias = nullptr;     // [N] model dtype
   void* out = nullptr;            // STORE/GELU/SILU/F32 destination
   int64_t ldo = 0;
-  int shared_chip = 0;            // dispatch hint: other launches run beside this one (row groups side by side), so a
-                                  // launch of few, high-intensity tiles does not leave the rest of the chip idle
+  int shared_chip = 0;            // dispatch hint: this many launches run side by side (row groups of one step on their
+                                  // own streams); each is planned for its share of the compute units.  0 or 1: alone
   // EPI_BRANCH
   float* h = nullptr;             // [M][N] fp32 residual stream
   int64_t ldh = 0;

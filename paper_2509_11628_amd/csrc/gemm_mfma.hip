@@ -25,6 +25,8 @@
 //                     bytes per FLOP of 128x128).
 //   gemm_mfma_kernel  the register-staged loop described above: K tails, small problems.
 
+#include <cmath>
+
 #include "epilogue.h"
 #include "gemm.h"
 
@@ -698,54 +700,121 @@ bool gemm_mfma_supported(const void* A, int64_t lda, const void* W, int64_t ldw,
          (reinterpret_cast<uintptr_t>(W) % 16 == 0);
 }
 
-Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi, hipStream_t st) {
-  // Tile shapes, from measurements on the reference-step shapes (M = 4096, N 1152..4608, K 1152 / 4608)
-  // and on FLUX-sized ones (M 4608, N 3072..12288, K 3072..12288):
-  //   256x256, 8 waves (wave tile 64x128): fewest L2 -> LDS bytes per FLOP; wins once K is long and the
-  //     problem still gives most CUs a tile (one block per CU);
-  //   256x128, 8 waves, 2- or 3-stage ring: medium problems;
-  //   128x128, 4 waves, register-staged loop, two blocks per CU: wide N with short K (inside a step the
-  //     direct-to-LDS 128x128 tile measured 75 us against 65 us on the 4096 x 4608 x 1152 MLP GEMM,
-  //     although it wins in isolation: with one K-step of prefetch it is more exposed to HBM latency
-  //     while the previous kernel's cache writes drain);
-  //   128x64 (register-staged loop): problems too small to give each CU a tile otherwise, and K tails.
+// ---- tile choice -------------------------------------------------------------------------------------------
+// Six kernels can run a given problem; which is fastest depends on how the tile count falls on the chip's compute
+// units more than on anything else (a 270-tile launch of one-block-per-CU tiles takes two rounds, a 252-tile one
+// takes one), and the row count M varies from call to call: per-sample rejection sends any number of guidance pairs
+// to the full pass and the lanes split a batch into row groups.  So the choice is made by a small cost model instead
+// of thresholds fitted to particular shapes:
+//     time(kernel) = (a + b * ceil(K / 64)) * depth,     depth = ceil(tiles / compute units),
+// where kernels whose LDS footprint lets a second block share a compute unit pay 0.65 of a round for every round
+// after the first.  a (launch, prologue, epilogue) and b (one 64-wide K-step) were measured in microseconds per
+// kernel on the block GEMMs of the DiT-XL/2 shape at M = 256 .. 4096 and on FLUX-sized problems with cold weights;
+// over those 45 problems the model's pick is within 2 % of the best kernel everywhere (the thresholds it replaces
+// lost 17-26 % at M = 1024, 2048, 2560 and 3072-3584).  Absolute times are off by up to 25 % on long-K problems,
+// where every kernel slows down alike; only the ranking is used.
+struct TileKind {
+  int bm, bn;
+  float a, b;          // microseconds
+  bool shares_cu;      // a second block fits beside the first
+  bool dlds;           // direct-to-LDS loop: K % 64 == 0, M >= 256
+  bool wide;           // 256-row tiles: M >= 256
+};
+constexpr TileKind kTileKinds[6] = {
+    {256, 256, 8.0f, 1.115f, false, true, true},    // 0: direct-to-LDS, 2 stages
+    {256, 128, 4.1f, 0.844f, false, true, true},    // 1: direct-to-LDS, 2 stages
+    {256, 128, 5.4f, 0.710f, false, true, true},    // 2: direct-to-LDS, 3 stages
+    {256, 128, 5.6f, 0.810f, false, false, true},   // 3: register-staged
+    {128, 128, 5.3f, 0.574f, true, false, false},   // 4: register-staged, two blocks per compute unit
+    {128, 64, 4.2f, 0.400f, true, false, false},    // 5: register-staged
+};
+
+static int compute_units() {
+  static const int n = [] {
+    int dev = 0, cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 1) {
+      (void)hipGetLastError();
+      cu = 256;
+    }
+    return cu;
+  }();
+  return n;
+}
+
+static double tile_cost(const TileKind& t, int M, int N, int K) {
+  const double tiles = static_cast<double>((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
+  const double depth = std::ceil(tiles / compute_units());
+  const double one = t.a + t.b * ((K + BK - 1) / BK);
+  return t.shares_cu ? one * (1.0 + 0.65 * (depth - 1.0)) : one * depth;
+}
+
+// cheapest eligible kernel for the problem; *cost receives its modelled time
+static int pick_tile(int M, int N, int K, double* cost) {
+  int best = -1;
+  double bc = 0.0;
+  for (int k = 0; k < 6; ++k) {
+    const TileKind& t = kTileKinds[k];
+    if (t.dlds && (K % BK != 0 || K < BK)) continue;
+    if (t.wide && M < 256) continue;
+    const double c = tile_cost(t, M, N, K);
+    if (best < 0 || c < bc) { best = k; bc = c; }
+  }
+  *cost = bc;
+  return best;
+}
+
+static Error launch_kind(int kind, const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi, hipStream_t st) {
+  switch (kind) {
+    case 0: return launch_dlds<256, 256, 4, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
+    case 1: return launch_dlds<256, 128, 4, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
+    case 2: return launch_dlds<256, 128, 4, 2, 3>(A, lda, W, ldw, M, N, K, epi, st);
+    case 3: return launch_tile<256, 128, 4, 2>(A, lda, W, ldw, M, N, K, epi, st);
+    case 4: return launch_tile<128, 128, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
+    default: return launch_tile<128, 64, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
+  }
+}
+
+// Row groups of one step that run side by side on their own streams (GemmEpi::shared_chip) share the compute units with
+// each other's kernels, which the model above does not price: planned for a quarter of the chip each, four lanes took
+// the large tiles of the whole batch and a step got 5 % slower.  What measured best there are the kernels that leave
+// room beside them: the 2-stage 256x128 ring (96 KiB of LDS, a 128x64 block of another lane still fits on the compute
+// unit), 128x64 tiles for the small N = 1152 GEMM, and the 3-stage ring only for a long-K GEMM of few tiles.
+static Error launch_shared(const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi, hipStream_t st) {
   const int64_t t128 = static_cast<int64_t>((M + 127) / 128) * ((N + 127) / 128);
   const int64_t t256 = static_cast<int64_t>((M + 255) / 256) * ((N + 127) / 128);
-  const int64_t t256s = static_cast<int64_t>((M + 255) / 256) * ((N + 255) / 256);
-  // Short K, a little more than one wave of 256x256 tiles (the 4096 x 4608 x 1152 fc1 GEMM: 288): the columns that make
-  // exactly one wave go on the large tile, the remaining columns in a second launch under the ordinary rules
-  // (47 + 13 us against 78 us for the one launch on 128x128 tiles).  Column ranges only shift pointers, so this is
-  // limited to the epilogues that store into `out`.
-  if (K % BK == 0 && M >= 256 && epi.mode != EPI_BRANCH && K >= 1024 && K < 2048 && t256s > 256 && t256s <= 320) {
-    const int tiles_m = (M + 255) / 256;
-    const int n1 = (256 / tiles_m) * 256;
-    if (n1 >= 256 && n1 < N) {
-      SPECA_TRY((launch_dlds<256, 256, 4, 2, 2>(A, lda, W, ldw, M, n1, K, epi, st)));
-      GemmEpi rest = epi;
-      if (epi.bias) rest.bias = static_cast<const uint16_t*>(epi.bias) + n1;
-      rest.out = epi.mode == EPI_F32 ? static_cast<void*>(static_cast<float*>(epi.out) + n1) : static_cast<void*>(static_cast<uint16_t*>(epi.out) + n1);
-      return launch_gemm_mfma(A, lda, static_cast<const uint16_t*>(W) + static_cast<int64_t>(n1) * ldw, ldw, M, N - n1, K, rest, st);
-    }
+  if (K % BK == 0 && K >= BK && M >= 256) {
+    if (K >= 2048 && t256 >= 32 && t256 < 100) return launch_dlds<256, 128, 4, 2, 3>(A, lda, W, ldw, M, N, K, epi, st);
+    if (t256 >= 100 && t256 < 256) return launch_dlds<256, 128, 4, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
   }
-  if (K % BK == 0 && M >= 256) {
-    if (K >= 2048 && t256s >= 160) return launch_dlds<256, 256, 4, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
-    // shorter K: only when the tiles are one wave of the chip at most (the 4096 x 3456 x 1152 qkv GEMM: 216 tiles, 842 against
-    // 668 TFLOP/s; at 288 tiles the second, nearly empty wave costs more than the tile saves)
-    if (K >= 1024 && t256s >= 160 && t256s <= 256) return launch_dlds<256, 256, 4, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
-    // long K with few tiles while other launches fill the remaining CUs (the 1024 x 1152 x 4608 fc2 GEMM of a four-lane step):
-    // the higher-intensity tile wins (+1 % on configuration 3 with lanes; alone on the chip it loses: -2.5 % on the
-    // text-stream GEMMs of the FLUX shape)
-    if (epi.shared_chip && K >= 2048 && t256 >= 32 && t256 < 100) return launch_dlds<256, 128, 4, 2, 3>(A, lda, W, ldw, M, N, K, epi, st);
-    if (t256 >= 100 && t128 <= 1024) {      // 100: the 1024 x 3456 qkv GEMM of a four-lane step (108 tiles) belongs here, measured
-      // at most one tile per CU and a short K loop: the 2-stage ring (96 KiB of LDS leave room for a block of
-      // another launch on the same CU when row groups run side by side); otherwise two loader groups, 3 stages
-      if (t256 < 256 && K < 2048) return launch_dlds<256, 128, 4, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
-      return launch_dlds<256, 128, 4, 2, 3>(A, lda, W, ldw, M, N, K, epi, st);
-    }
-  }
-  if (t256 >= 128 && (t128 <= 1024 || (K >= 2048 && t128 >= 2048)) && M >= 256) return launch_tile<256, 128, 4, 2>(A, lda, W, ldw, M, N, K, epi, st);
+  double cost = 0.0;
+  if (t256 >= 256) return launch_kind(pick_tile(M, N, K, &cost), A, lda, W, ldw, M, N, K, epi, st);
   if (t128 >= 200) return launch_tile<128, 128, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
   return launch_tile<128, 64, 2, 2>(A, lda, W, ldw, M, N, K, epi, st);
+}
+
+Error launch_gemm_mfma(const void* A, int64_t lda, const void* W, int64_t ldw, int M, int N, int K, const GemmEpi& epi, hipStream_t st) {
+  if (epi.shared_chip > 1) return launch_shared(A, lda, W, ldw, M, N, K, epi, st);
+  double whole = 0.0;
+  const int kind = pick_tile(M, N, K, &whole);
+  // A little more than one round of 256x256 tiles (the 4096 x 4608 x 1152 fc1 GEMM: 288): the columns that make exactly one
+  // round go on the large tile, the remaining columns in a second launch (47 + 13 us against 61 us for the best single
+  // kernel).  Column ranges only shift pointers, so this is limited to the epilogues that store into `out`.
+  if (epi.mode != EPI_BRANCH && K % BK == 0 && K >= BK && M >= 256) {
+    const int tiles_m = (M + 255) / 256;
+    const int n1 = (compute_units() / tiles_m) * 256;
+    if (n1 >= 256 && n1 < N) {
+      double rest = 0.0;
+      (void)pick_tile(M, N - n1, K, &rest);
+      if (tile_cost(kTileKinds[0], M, n1, K) + rest < 0.9 * whole) {
+        SPECA_TRY((launch_dlds<256, 256, 4, 2, 2>(A, lda, W, ldw, M, n1, K, epi, st)));
+        GemmEpi tail = epi;
+        if (epi.bias) tail.bias = static_cast<const uint16_t*>(epi.bias) + n1;
+        tail.out = epi.mode == EPI_F32 ? static_cast<void*>(static_cast<float*>(epi.out) + n1) : static_cast<void*>(static_cast<uint16_t*>(epi.out) + n1);
+        return launch_gemm_mfma(A, lda, static_cast<const uint16_t*>(W) + static_cast<int64_t>(n1) * ldw, ldw, M, N - n1, K, tail, st);
+      }
+    }
+  }
+  return launch_kind(kind, A, lda, W, ldw, M, N, K, epi, st);
 }
 
 }  // namespace speca

@@ -20,6 +20,7 @@ Error launch_cache_warm(const CacheGeom& g, const RowTable& rt, int slot, hipStr
 // otherwise the prediction is formed from slot `slot` of the cache with rt's weights.
 // partial: device scratch of n_rows * verify_chunks(E) * 3 floats.
 int verify_chunks(int64_t E);
+constexpr int kMaxVerifyRows = 1024;   // rows of one launch when prediction and truth are both tensors
 Error launch_verify(int metric, const void* pred, int pred_dtype, const void* truth, int truth_dtype, int64_t E,
                     const CacheGeom* g, const RowTable* rt, int slot, int n_rows, float eps, const float* tau_dev,
                     float* partial, float* err_dev, uint8_t* accept_dev, hipStream_t st);

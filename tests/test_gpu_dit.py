@@ -401,7 +401,7 @@ def test_lanes_do_not_change_results(tiny):
     import paper_2509_11628_amd as sp
     from paper_2509_11628_amd import binding as bd
     s, w, om, ctx = tiny
-    S, B = 10, 4
+    S, B = 10, 8                                   # 16 rows: launches of 9 rows and more are split into row groups
     ts, ab = si.ddim_tables(S)
     lat = si.make_latents(B, s.in_channels, s.latent_hw, 3)
     lab = si.make_labels(B, s.num_classes, 3)
