@@ -400,7 +400,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="configuration 3 only (no configuration 2 / 4 / 5 runs, no sweeps)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the configured, event-profiled, plain and all-accepted trajectories of configuration 3 (profiling runs)")
     ap.add_argument("--tau0", type=float, default=0.1)
     ap.add_argument("--tau-end", type=float, default=0.02)
     ap.add_argument("--interval", type=int, default=5)
@@ -483,8 +484,8 @@ def main():
 
     # images/s is defined on the 50-step trajectory the configuration names, whatever --steps was
     S50 = 50
-    if K == S50:
-        dt50, dt50_plain = dt, dt_plain
+    if K == S50 or args.no_extras:
+        dt50, dt50_plain = dt * S50 / K, dt_plain * S50 / K
     else:
         run(S50)
         dt50, _, _, _ = run(S50)
@@ -492,57 +493,65 @@ def main():
     extras["images_per_s"] = B / dt50
     extras["images_per_s_note"] = f"{B} images per {S50}-step trajectory as configured ({dt50 * 1e3:.0f} ms); plain sampling {B / dt50_plain:.1f} images/s"
 
-    # Thresholds at which the seeded model accepts part of its attempts (0 < alpha < 1): the geometric schedule with the
-    # paper's DiT ablation value tau0 = 0.3, decaying to 0.1, calibrated once on this model (its verification errors
-    # run from 0.04 to 0.33); and the same threshold level on latents scaled per sample (0.4 .. 2.0), whose errors
-    # differ enough that most steps split the batch into a speculative and a full row list.
-    tau_cal = bd.tau_geometric(0.3, 0.1 / 0.3, S50)
-    run(S50, tau=tau_cal)
-    dt_cal, tr_cal, _, x_cal = run(S50, tau=tau_cal)
-    scales = np.array([0.4, 0.5, 0.6, 0.7, 1.4, 1.6, 1.8, 2.0], np.float32)
-    lat_sc = lat * scales[:, None, None, None]
-    tau_mix = np.full(S50, 0.2, np.float32)
-    dt_mix, tr_mix, _, x_mix = run(S50, tau=tau_mix, latents=lat_sc)
-    dt_mix_plain, _, _, _ = run(S50, tau=np.zeros(S50, np.float32), latents=lat_sc)
-    assert bool(torch.isfinite(x_cal).all()) and bool(torch.isfinite(x_mix).all())
-    mixed_steps = sum(1 for s_ in range(S50) if len(set(tr_mix["kind"][:, s_].tolist())) > 1)
-    if K != S50:
-        dt50_acc, tr50_acc, _, _ = run(S50, tau=np.full(S50, np.inf, np.float32))
+    if args.no_extras:
+        # profiling runs: only the four trajectories above (configured, event-profiled, plain, all accepted)
+        t_full = dt_plain / K
+        a_acc = tr_acc["n_spec"] / float(B * K)
+        c_s = (dt_acc / K - (1.0 - a_acc) * t_full) / (a_acc * t_full)
+        extras["speedup_model"] = {"gamma_nominal": 1.0 / shape.depth, "accepted_step_cost_ratio_measured": c_s,
+                                   "all_accepted": {"alpha": a_acc, "measured_vs_plain": dt_plain / dt_acc}}
     else:
-        dt50_acc, tr50_acc = dt_acc, tr_acc
+        # Thresholds at which the seeded model accepts part of its attempts (0 < alpha < 1): the geometric schedule with the
+        # paper's DiT ablation value tau0 = 0.3, decaying to 0.1, calibrated once on this model (its verification errors
+        # run from 0.04 to 0.33); and the same threshold level on latents scaled per sample (0.4 .. 2.0), whose errors
+        # differ enough that most steps split the batch into a speculative and a full row list.
+        tau_cal = bd.tau_geometric(0.3, 0.1 / 0.3, S50)
+        run(S50, tau=tau_cal)
+        dt_cal, tr_cal, _, x_cal = run(S50, tau=tau_cal)
+        scales = np.array([0.4, 0.5, 0.6, 0.7, 1.4, 1.6, 1.8, 2.0], np.float32)
+        lat_sc = lat * scales[:, None, None, None]
+        tau_mix = np.full(S50, 0.2, np.float32)
+        dt_mix, tr_mix, _, x_mix = run(S50, tau=tau_mix, latents=lat_sc)
+        dt_mix_plain, _, _, _ = run(S50, tau=np.zeros(S50, np.float32), latents=lat_sc)
+        assert bool(torch.isfinite(x_cal).all()) and bool(torch.isfinite(x_mix).all())
+        mixed_steps = sum(1 for s_ in range(S50) if len(set(tr_mix["kind"][:, s_].tolist())) > 1)
+        if K != S50:
+            dt50_acc, tr50_acc, _, _ = run(S50, tau=np.full(S50, np.inf, np.float32))
+        else:
+            dt50_acc, tr50_acc = dt_acc, tr_acc
 
-    # Speed-up model of the paper's complexity analysis, S = 1 / (1 - alpha (1 - gamma - overhead)), extended by the
-    # attempts that are rejected (the paper's count charges only accepted steps): with c_s = cost of an accepted
-    # speculative step and c_r = cost of a rejected attempt, both relative to a full step, and rho = rejected
-    # attempts per sample-step,  S = 1 / ((1 - alpha) + alpha c_s + rho c_r).  c_s is measured on the all-accepted run,
-    # c_r on the all-rejected run (the configured thresholds), both against plain sampling of the same length.
-    def ratios(d_run, trc, d_plain, steps):
-        return trc["n_spec"] / float(B * steps), trc["n_reject"] / float(B * steps), d_plain / d_run
-    t_full = dt50_plain / S50
-    a_acc, _, s_acc = ratios(dt50_acc, tr50_acc, dt50_plain, S50)
-    c_s = (dt50_acc / S50 - (1.0 - a_acc) * t_full) / (a_acc * t_full)
-    a_cfg, r_cfg, s_cfg = ratios(dt, tr, dt_plain, K)
-    c_r = (dt / K - (1.0 - a_cfg) * (dt_plain / K) - a_cfg * c_s * (dt_plain / K)) / max(r_cfg, 1e-9) / (dt_plain / K)
-    gamma = 1.0 / shape.depth
+        # Speed-up model of the paper's complexity analysis, S = 1 / (1 - alpha (1 - gamma - overhead)), extended by the
+        # attempts that are rejected (the paper's count charges only accepted steps): with c_s = cost of an accepted
+        # speculative step and c_r = cost of a rejected attempt, both relative to a full step, and rho = rejected
+        # attempts per sample-step,  S = 1 / ((1 - alpha) + alpha c_s + rho c_r).  c_s is measured on the all-accepted run,
+        # c_r on the all-rejected run (the configured thresholds), both against plain sampling of the same length.
+        def ratios(d_run, trc, d_plain, steps):
+            return trc["n_spec"] / float(B * steps), trc["n_reject"] / float(B * steps), d_plain / d_run
+        t_full = dt50_plain / S50
+        a_acc, _, s_acc = ratios(dt50_acc, tr50_acc, dt50_plain, S50)
+        c_s = (dt50_acc / S50 - (1.0 - a_acc) * t_full) / (a_acc * t_full)
+        a_cfg, r_cfg, s_cfg = ratios(dt, tr, dt_plain, K)
+        c_r = (dt / K - (1.0 - a_cfg) * (dt_plain / K) - a_cfg * c_s * (dt_plain / K)) / max(r_cfg, 1e-9) / (dt_plain / K)
+        gamma = 1.0 / shape.depth
 
-    def predict(a, r):
-        return {"paper_nominal": 1.0 / (1.0 - a * (1.0 - gamma)), "with_measured_costs": 1.0 / ((1.0 - a) + a * c_s + r * c_r)}
-    a_cal, r_cal, s_cal = ratios(dt_cal, tr_cal, dt50_plain, S50)
-    a_mix, r_mix, s_mix = ratios(dt_mix, tr_mix, dt_mix_plain, S50)
-    extras["speedup_model"] = {
-        "gamma_nominal": gamma, "accepted_step_cost_ratio_measured": c_s, "rejected_attempt_cost_ratio_measured": c_r,
-        "as_configured": {"alpha": a_cfg, "rejected_attempts_per_step": r_cfg, "predicted": predict(a_cfg, r_cfg), "measured_vs_plain": s_cfg},
-        "all_accepted": {"alpha": a_acc, "rejected_attempts_per_step": 0.0, "predicted": predict(a_acc, 0.0), "measured_vs_plain": s_acc},
-        "calibrated_thresholds": {"alpha": a_cal, "rejected_attempts_per_step": r_cal, "predicted": predict(a_cal, r_cal), "measured_vs_plain": s_cal},
-        "mixed_rows": {"alpha": a_mix, "rejected_attempts_per_step": r_mix, "predicted": predict(a_mix, r_mix), "measured_vs_plain": s_mix,
-                       "note": "the prediction assumes whole-batch launches; a step that splits the batch pays a full pass at a smaller, less efficient M"},
-    }
-    extras["calibrated_thresholds_run"] = {"tau": "geometric 0.3 -> 0.1 over 50 steps", "steps_per_s": S50 / dt_cal, "images_per_s": B / dt_cal,
-                                           "accept_rate": a_cal, "n_full": tr_cal["n_full"], "n_spec": tr_cal["n_spec"], "n_reject": tr_cal["n_reject"]}
-    extras["mixed_rows_run"] = {"tau": "0.2 constant, latents of sample b scaled by (0.4, 0.5, 0.6, 0.7, 1.4, 1.6, 1.8, 2.0)[b]", "steps_per_s": S50 / dt_mix,
-                                "plain_sampling_steps_per_s": S50 / dt_mix_plain, "accept_rate": a_mix, "n_full": tr_mix["n_full"],
-                                "n_spec": tr_mix["n_spec"], "n_reject": tr_mix["n_reject"], "steps_that_split_the_batch": mixed_steps}
-    _log(f"calibrated thresholds: alpha {a_cal:.2f}, {S50 / dt_cal:.1f} steps/s; mixed rows: alpha {a_mix:.2f}, {S50 / dt_mix:.1f} steps/s, {mixed_steps} split steps")
+        def predict(a, r):
+            return {"paper_nominal": 1.0 / (1.0 - a * (1.0 - gamma)), "with_measured_costs": 1.0 / ((1.0 - a) + a * c_s + r * c_r)}
+        a_cal, r_cal, s_cal = ratios(dt_cal, tr_cal, dt50_plain, S50)
+        a_mix, r_mix, s_mix = ratios(dt_mix, tr_mix, dt_mix_plain, S50)
+        extras["speedup_model"] = {
+            "gamma_nominal": gamma, "accepted_step_cost_ratio_measured": c_s, "rejected_attempt_cost_ratio_measured": c_r,
+            "as_configured": {"alpha": a_cfg, "rejected_attempts_per_step": r_cfg, "predicted": predict(a_cfg, r_cfg), "measured_vs_plain": s_cfg},
+            "all_accepted": {"alpha": a_acc, "rejected_attempts_per_step": 0.0, "predicted": predict(a_acc, 0.0), "measured_vs_plain": s_acc},
+            "calibrated_thresholds": {"alpha": a_cal, "rejected_attempts_per_step": r_cal, "predicted": predict(a_cal, r_cal), "measured_vs_plain": s_cal},
+            "mixed_rows": {"alpha": a_mix, "rejected_attempts_per_step": r_mix, "predicted": predict(a_mix, r_mix), "measured_vs_plain": s_mix,
+                           "note": "the prediction assumes whole-batch launches; a step that splits the batch pays a full pass at a smaller, less efficient M"},
+        }
+        extras["calibrated_thresholds_run"] = {"tau": "geometric 0.3 -> 0.1 over 50 steps", "steps_per_s": S50 / dt_cal, "images_per_s": B / dt_cal,
+                                               "accept_rate": a_cal, "n_full": tr_cal["n_full"], "n_spec": tr_cal["n_spec"], "n_reject": tr_cal["n_reject"]}
+        extras["mixed_rows_run"] = {"tau": "0.2 constant, latents of sample b scaled by (0.4, 0.5, 0.6, 0.7, 1.4, 1.6, 1.8, 2.0)[b]", "steps_per_s": S50 / dt_mix,
+                                    "plain_sampling_steps_per_s": S50 / dt_mix_plain, "accept_rate": a_mix, "n_full": tr_mix["n_full"],
+                                    "n_spec": tr_mix["n_spec"], "n_reject": tr_mix["n_reject"], "steps_that_split_the_batch": mixed_steps}
+        _log(f"calibrated thresholds: alpha {a_cal:.2f}, {S50 / dt_cal:.1f} steps/s; mixed rows: alpha {a_mix:.2f}, {S50 / dt_mix:.1f} steps/s, {mixed_steps} split steps")
 
     cpu = None if args.no_cpu_baseline else cpu_baseline(shape, weights)
     ctx.close()
