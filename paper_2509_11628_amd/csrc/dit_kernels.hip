@@ -172,15 +172,19 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 // enters the verify block and the one the accepted path finishes from come out of one pass over the cache.
 // gate of slot j for compact row i: mod[i * mod_stride + gate_off[2j + s] + d], s = 0 for elements below
 // split_elem (the text tokens of a two-stream block), 1 from there on.
-template <typename T, int NT>
+// A thread owns 8 consecutive elements at each of TOK positions half a row apart (TOK = 2 needs an even number of
+// tokens: both positions then have the same channel d, and, when no stream boundary falls inside the row, the same
+// gate: one gate load serves two sets of cache loads; the gates are 40 % of the load instructions otherwise).
+template <typename T, int NT, int TOK, int UNROLL>
 __global__ __launch_bounds__(256) void forecast_fold_kernel(CacheGeom g, RowTable rt, const float* h_in,   // h_in may be h_out (in place)
                                                             float* h_out, float* h_mid, int s_mid, const float* __restrict__ mod,
                                                             int64_t mod_stride, const int32_t* __restrict__ gate_off, int64_t split_elem,
                                                             int s0, int s1, int D) {
-  constexpr int V = 8;     // 8 elements per thread: 2 x 16 B of fp32 hidden, 16 B (bf16) or 2 x 16 B (fp32) of every cached tensor
+  constexpr int V = 8;     // 8 elements per position: 2 x 16 B of fp32 hidden, 16 B (bf16) or 2 x 16 B (fp32) of every cached tensor
   const int i = blockIdx.y;
+  const int64_t EP = g.E / TOK;                                                // distance of a thread's positions
   const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * V;
-  if (e >= g.E) return;
+  if (e >= EP) return;
   const int d = static_cast<int>(e % D);
   const int row = rt.row[i];
   const int order = rt.order[i];
@@ -194,53 +198,70 @@ __global__ __launch_bounds__(256) void forecast_fold_kernel(CacheGeom g, RowTabl
     oc[o] = o <= order ? o : order;
   }
   const T* base = static_cast<const T*>(g.base);
-  const float* hp = h_in + static_cast<int64_t>(i) * g.E + e;
-  const float4 h0 = *reinterpret_cast<const float4*>(hp), h1 = *reinterpret_cast<const float4*>(hp + 4);
-  float acc[V] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+  float acc[TOK][V];
+#pragma unroll
+  for (int t = 0; t < TOK; ++t) {
+    const float* hp = h_in + static_cast<int64_t>(i) * g.E + e + t * EP;
+    const float4 h0 = *reinterpret_cast<const float4*>(hp), h1 = *reinterpret_cast<const float4*>(hp + 4);
+    acc[t][0] = h0.x; acc[t][1] = h0.y; acc[t][2] = h0.z; acc[t][3] = h0.w;
+    acc[t][4] = h1.x; acc[t][5] = h1.y; acc[t][6] = h1.z; acc[t][7] = h1.w;
+  }
   const float* mrow = mod + static_cast<int64_t>(i) * mod_stride + d;
-  const bool sel = e >= split_elem;
-  // four slots per trip: 4 * NT cache loads in flight per lane (measured best among 1/2/4/8)
+  const bool sel = e >= split_elem;                                           // TOK > 1 is only launched when this holds for a whole row
+  auto store = [&](float* dst) {
+#pragma unroll
+    for (int t = 0; t < TOK; ++t) {
+      float* p = dst + static_cast<int64_t>(i) * g.E + e + t * EP;
+      *reinterpret_cast<float4*>(p) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
+      *reinterpret_cast<float4*>(p + 4) = make_float4(acc[t][4], acc[t][5], acc[t][6], acc[t][7]);
+    }
+  };
+  // TOK * UNROLL * NT cache loads in flight per lane (measured best: 12 with one position, 6 with two)
   auto fold = [&](int sa, int sb) {
-#pragma unroll 4
+#pragma unroll UNROLL
     for (int slot = sa; slot < sb; ++slot) {
       const int off0 = gate_off[2 * slot], off1 = gate_off[2 * slot + 1];     // block-uniform: scalar loads
       const float* gp = mrow + (sel ? off1 : off0);
       const float4 g0 = *reinterpret_cast<const float4*>(gp), g1 = *reinterpret_cast<const float4*>(gp + 4);
       const float gg[V] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
-      float f[V];
+      float t8[TOK][NT][V];
 #pragma unroll
-      for (int q = 0; q < V; ++q) f[q] = 0.0f;
+      for (int t = 0; t < TOK; ++t)
 #pragma unroll
-      for (int o = 0; o < NT; ++o) {
-        float t8[V];
-        const T* p = base + g.offset(slot, oc[o], row) + e;
-        if (sizeof(T) == 2) {
-          const u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));     // read once per step: keep it out of the caches' way
+        for (int o = 0; o < NT; ++o) {
+          const T* p = base + g.offset(slot, oc[o], row) + e + t * EP;
+          if (sizeof(T) == 2) {
+            const u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));     // read once per step: keep it out of the caches' way
 #pragma unroll
-          for (int q = 0; q < 4; ++q) { t8[2 * q] = __uint_as_float(r[q] << 16); t8[2 * q + 1] = __uint_as_float(r[q] & 0xFFFF0000u); }
-        } else {
-          const float4 r0 = *reinterpret_cast<const float4*>(p), r1 = *reinterpret_cast<const float4*>(p + 4);
-          t8[0] = r0.x; t8[1] = r0.y; t8[2] = r0.z; t8[3] = r0.w; t8[4] = r1.x; t8[5] = r1.y; t8[6] = r1.z; t8[7] = r1.w;
+            for (int q = 0; q < 4; ++q) { t8[t][o][2 * q] = __uint_as_float(r[q] << 16); t8[t][o][2 * q + 1] = __uint_as_float(r[q] & 0xFFFF0000u); }
+          } else {
+            const float4 r0 = *reinterpret_cast<const float4*>(p), r1 = *reinterpret_cast<const float4*>(p + 4);
+            t8[t][o][0] = r0.x; t8[t][o][1] = r0.y; t8[t][o][2] = r0.z; t8[t][o][3] = r0.w;
+            t8[t][o][4] = r1.x; t8[t][o][5] = r1.y; t8[t][o][6] = r1.z; t8[t][o][7] = r1.w;
+          }
         }
 #pragma unroll
-        for (int q = 0; q < V; ++q) f[q] = fmaf(c[o], t8[q], f[q]);
-      }
+      for (int t = 0; t < TOK; ++t) {
+        float f[V];
 #pragma unroll
-      for (int q = 0; q < V; ++q) acc[q] = fmaf(gg[q], f[q], acc[q]);
+        for (int q = 0; q < V; ++q) f[q] = 0.0f;
+#pragma unroll
+        for (int o = 0; o < NT; ++o)
+#pragma unroll
+          for (int q = 0; q < V; ++q) f[q] = fmaf(c[o], t8[t][o][q], f[q]);
+#pragma unroll
+        for (int q = 0; q < V; ++q) acc[t][q] = fmaf(gg[q], f[q], acc[t][q]);
+      }
     }
   };
   if (h_mid) {                                                                // block-uniform
     fold(s0, s_mid);
-    float* mp = h_mid + static_cast<int64_t>(i) * g.E + e;
-    *reinterpret_cast<float4*>(mp) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-    *reinterpret_cast<float4*>(mp + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    store(h_mid);
     fold(s_mid, s1);
   } else {
     fold(s0, s1);
   }
-  float* op = h_out + static_cast<int64_t>(i) * g.E + e;
-  *reinterpret_cast<float4*>(op) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-  *reinterpret_cast<float4*>(op + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+  store(h_out);
 }
 
 // model_out[row][c][i*p+pi][j*p+pj] = tok[i_compact][t=(i,j)][(c,pi,pj)]
@@ -324,8 +345,15 @@ Error launch_ln_modulate2(int dtype, const float* h, const float* shift, const f
 template <typename T, int NT>
 static Error fold_launch(const CacheGeom& g, const RowTable& rt, const float* h_in, float* h_out, float* h_mid, int s_mid, const float* mod,
                          int64_t mod_stride, const int32_t* gate_off, int64_t split_elem, int s0, int s1, int D, hipStream_t st) {
-  const dim3 grid(blocks_for(g.E, 256 * 8), rt.n);
-  forecast_fold_kernel<T, NT><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, h_mid, s_mid, mod, mod_stride, gate_off, split_elem, s0, s1, D);
+  // two positions per thread when both see the same channel and the same gate: an even number of tokens, no stream boundary inside the row
+  const bool two = g.E % (2 * static_cast<int64_t>(D)) == 0 && (split_elem == 0 || split_elem >= g.E);
+  if (two) {
+    const dim3 grid(blocks_for(g.E / 2, 256 * 8), rt.n);
+    forecast_fold_kernel<T, NT, 2, 1><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, h_mid, s_mid, mod, mod_stride, gate_off, split_elem >= g.E ? g.E : 0, s0, s1, D);
+  } else {
+    const dim3 grid(blocks_for(g.E, 256 * 8), rt.n);
+    forecast_fold_kernel<T, NT, 1, 4><<<grid, 256, 0, st>>>(g, rt, h_in, h_out, h_mid, s_mid, mod, mod_stride, gate_off, split_elem, s0, s1, D);
+  }
   SPECA_HIP(hipGetLastError());
   return ok();
 }
