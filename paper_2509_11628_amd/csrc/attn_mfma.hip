@@ -540,6 +540,12 @@ __global__ __launch_bounds__(256, 2) void attention_dma_kernel(const uint16_t* _
 // takes the softmax in one pass (no running maximum, no rescaling of O) and runs the second
 // contraction over all keys.  At 256 tokens the tiled kernels spend their time in per-tile load
 // latency and barriers; this form is bound by one load round trip plus ~90 MFMAs per wave.
+constexpr size_t whole_lds_bytes(int HD, bool stage) {
+  const int HD16 = (HD + 15) / 16 * 16, HD32 = (HD + 31) / 32 * 32;
+  return (static_cast<size_t>(256) * (HD16 + 8) + static_cast<size_t>(HD32) * 256 + (stage ? static_cast<size_t>(8) * 32 * HD : 0)) * sizeof(uint16_t);
+}
+constexpr bool whole_stages_output(int HD) { return whole_lds_bytes(HD, true) <= 160 * 1024; }
+
 template <int HD>
 __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_t* __restrict__ qkv, uint16_t* __restrict__ out, int64_t ldo,
                                                                    int T, int H, float scale_log2e) {
@@ -556,8 +562,14 @@ __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_
   extern __shared__ __align__(16) uint16_t smem[];
   uint16_t* Ks = smem;                        // [TMAX][KST]
   uint16_t* Vt = smem + TMAX * KST;           // [HD32][TMAX], see vt_read_off
+  uint16_t* Os = Vt + HD32 * TMAX;            // [8 waves][32 queries][HD]: output staging, private to a wave (STAGE_OUT)
+  constexpr bool STAGE_OUT = whole_stages_output(HD);
 
-  const int row = blockIdx.z, head = blockIdx.y;
+  // blocks b, b + 8, b + 16, ... run on the same XCD: give each XCD a contiguous range of (row, head) pairs, so
+  // that a row's q, k and v are pulled into one L2 instead of a slice of every row into all eight
+  const int lin = blockIdx.y + gridDim.y * blockIdx.z, total = gridDim.y * gridDim.z;
+  const int pair = total % 8 == 0 ? (lin % 8) * (total / 8) + lin / 8 : lin;
+  const int row = pair / H, head = pair - row * H;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lhi = lane >> 5;
   const int64_t D = static_cast<int64_t>(H) * HD;
@@ -683,20 +695,49 @@ __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_
   }
   const float ltot = psum + __shfl_xor(psum, 32, 64);
   const float inv = 1.0f / ltot;
-  if (q < T) {
-    uint16_t* op = out + (static_cast<int64_t>(row) * T + q) * ldo + head * HD;
+  // A lane holds one query's output in 8-byte pieces 2304 bytes apart from its neighbour's: the wave re-lays its
+  // 32 x HD tile through its own piece of LDS and stores whole 16-byte chunks, a query's HD values contiguous.
+  if (!STAGE_OUT) {                            // no LDS to spare: 8-byte stores straight from the accumulators
+    if (q < T) {
+      uint16_t* op = out + (static_cast<int64_t>(row) * T + q) * ldo + head * HD;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+      for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int d = dt * 32 + 8 * jj + 4 * lhi;
-        if (d < HD) {
-          uint2 r;
-          r.x = cvt_pk_bf16(o[dt][4 * jj] * inv, o[dt][4 * jj + 1] * inv);
-          r.y = cvt_pk_bf16(o[dt][4 * jj + 2] * inv, o[dt][4 * jj + 3] * inv);
-          *reinterpret_cast<uint2*>(op + d) = r;
+        for (int jj = 0; jj < 4; ++jj) {
+          const int d = dt * 32 + 8 * jj + 4 * lhi;
+          if (d < HD) {
+            uint2 r;
+            r.x = cvt_pk_bf16(o[dt][4 * jj] * inv, o[dt][4 * jj + 1] * inv);
+            r.y = cvt_pk_bf16(o[dt][4 * jj + 2] * inv, o[dt][4 * jj + 3] * inv);
+            *reinterpret_cast<uint2*>(op + d) = r;
+          }
         }
+    }
+    return;
+  }
+  uint16_t* ow = Os + wave * 32 * HD;
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const int d = dt * 32 + 8 * jj + 4 * lhi;
+      if (d < HD) {
+        uint2 r;
+        r.x = cvt_pk_bf16(o[dt][4 * jj] * inv, o[dt][4 * jj + 1] * inv);
+        r.y = cvt_pk_bf16(o[dt][4 * jj + 2] * inv, o[dt][4 * jj + 3] * inv);
+        *reinterpret_cast<uint2*>(ow + l32 * HD + d) = r;
       }
+    }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");       // the wave's LDS writes before its reads below
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  uint16_t* ob = out + (static_cast<int64_t>(row) * T + wave * 32) * ldo + head * HD;
+#pragma unroll
+  for (int c0 = 0; c0 < 32 * CH; c0 += 64) {
+    const int c = c0 + lane;
+    const int qq = c / CH, dc = c - qq * CH;
+    if (c < 32 * CH && wave * 32 + qq < T)
+      *reinterpret_cast<uint4*>(ob + static_cast<int64_t>(qq) * ldo + dc * 8) = *reinterpret_cast<const uint4*>(ow + qq * HD + dc * 8);
   }
 }
 
@@ -704,8 +745,9 @@ template <int HD>
 Error launch_hd(const void* qkv, void* out, int64_t ldo, int rows, int T, int H, hipStream_t st) {
   constexpr int HD16 = (HD + 15) / 16 * 16, HD32 = (HD + 31) / 32 * 32;
   const size_t smem = static_cast<size_t>(2) * (64 * (HD16 + 8) + HD32 * 64) * sizeof(uint16_t);
-  if (T <= 256) {
-    constexpr size_t smem_w = (static_cast<size_t>(256) * (HD16 + 8) + static_cast<size_t>(HD32) * 256) * sizeof(uint16_t);
+  // (the whole-sequence kernel stores 16-byte chunks of the output when it stages them through LDS)
+  if (T <= 256 && (!whole_stages_output(HD) || (ldo % 8 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0))) {
+    constexpr size_t smem_w = whole_lds_bytes(HD, whole_stages_output(HD));
     static bool attr_w = false;
     if (smem_w > 64 * 1024 && !attr_w) {
       SPECA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attention_mfma_whole_kernel<HD>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem_w)));
