@@ -546,10 +546,13 @@ constexpr size_t whole_lds_bytes(int HD, bool stage) {
 }
 constexpr bool whole_stages_output(int HD) { return whole_lds_bytes(HD, true) <= 160 * 1024; }
 
-template <int HD>
+// FULL: T == 256 exactly (the DiT-XL/2 shape): no bounds tests, no ragged sub-tile, so the two contractions and the
+// softmax between them are one straight-line region that the scheduler can interleave.
+template <int HD, bool FULL>
 __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_t* __restrict__ qkv, uint16_t* __restrict__ out, int64_t ldo,
-                                                                   int T, int H, float scale_log2e) {
+                                                                   int T_, int H, float scale_log2e) {
   constexpr int TMAX = 256;
+  const int T = FULL ? TMAX : T_;
   constexpr int HD16 = (HD + 15) / 16 * 16, HD32 = (HD + 31) / 32 * 32;
   constexpr int KS = HD16 / 16;         // reduction steps of q k^T
   constexpr int DT = HD32 / 32;         // 32-row tiles of O^T
@@ -603,8 +606,11 @@ __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_
   // zero padding: key columns [HD, HD16) and value rows [HD, HD32)
   if (HD16 > HD)
     for (int i = tid; i < TMAX * (HD16 - HD); i += 512) Ks[(i / (HD16 - HD)) * KST + HD + i % (HD16 - HD)] = 0;
+  // (with a spare row, row HD of V^T is all ones: row HD of O^T is then the sum of the probabilities as the matrix
+  // cores saw them, rounded to bf16 like the numerator)
+  constexpr bool ONES = HD32 > HD;
   if (HD32 > HD)
-    for (int i = tid; i < (HD32 - HD) * TMAX; i += 512) Vt[HD * TMAX + i] = 0;
+    for (int i = tid; i < (HD32 - HD) * TMAX; i += 512) Vt[HD * TMAX + i] = i < TMAX ? 0x3F80 : 0;
 #pragma unroll
   for (int c = 0; c < K_CHUNKS; ++c) {
     const int id = tid + c * 512;
@@ -632,9 +638,9 @@ __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_
     }
   }
   __syncthreads();
-  if (wave * 32 >= T) return;                  // no barrier after this point
+  if (!FULL && wave * 32 >= T) return;         // no barrier after this point
 
-  const int nst = (T + 31) / 32;               // sub-tiles that hold keys
+  const int nst = FULL ? NST : (T + 31) / 32;  // sub-tiles that hold keys
   floatx16 s[NST];
   float tmax = -INFINITY;
 #pragma unroll
@@ -663,37 +669,42 @@ __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_
   tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));     // maximum of the raw scores; scale and log2(e) enter in the fma below
   const float moff = tmax * scale_log2e;
   float psum = 0.0f;
+  auto exps = [&](int st) {                      // probabilities of one sub-tile, in place
 #pragma unroll
-  for (int st = 0; st < NST; ++st)
-    if (st < nst) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const float p = fast_exp2(fmaf(s[st][e], scale_log2e, -moff));
-        s[st][e] = p;
-        psum += p;
-      }
+    for (int e = 0; e < 16; ++e) {
+      const float p = fast_exp2(fmaf(s[st][e], scale_log2e, -moff));
+      s[st][e] = p;
+      if (!ONES) psum += p;
     }
+  };
   floatx16 o[DT];
 #pragma unroll
   for (int i = 0; i < DT; ++i)
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[i][e] = 0.0f;
+  // the exponentials of sub-tile st + 1 are issued with the second contraction of sub-tile st
+  if (0 < nst) exps(0);
 #pragma unroll
-  for (int t = 0; t < 2 * NST; ++t) {
-    const int st = t >> 1, j0 = (t & 1) * 8;      // accumulator entries j0 .. j0+7 of sub-tile st: 16 keys
+  for (int st = 0; st < NST; ++st) {
     if (st < nst) {
-      Frag pf;
-      pf.u = make_uint4(cvt_pk_bf16(s[st][j0], s[st][j0 + 1]), cvt_pk_bf16(s[st][j0 + 2], s[st][j0 + 3]),
-                        cvt_pk_bf16(s[st][j0 + 4], s[st][j0 + 5]), cvt_pk_bf16(s[st][j0 + 6], s[st][j0 + 7]));
+      if (st + 1 < NST && st + 1 < nst) exps(st + 1);
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        Frag vf;
-        vf.u = *reinterpret_cast<const uint4*>(Vt + vt_read_off<TMAX>(dt * 32 + l32, t, lhi));
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[dt], 0, 0, 0);
+      for (int hh = 0; hh < 2; ++hh) {
+        const int t = 2 * st + hh, j0 = hh * 8;   // accumulator entries j0 .. j0+7 of sub-tile st: 16 keys
+        Frag pf;
+        pf.u = make_uint4(cvt_pk_bf16(s[st][j0], s[st][j0 + 1]), cvt_pk_bf16(s[st][j0 + 2], s[st][j0 + 3]),
+                          cvt_pk_bf16(s[st][j0 + 4], s[st][j0 + 5]), cvt_pk_bf16(s[st][j0 + 6], s[st][j0 + 7]));
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          Frag vf;
+          vf.u = *reinterpret_cast<const uint4*>(Vt + vt_read_off<TMAX>(dt * 32 + l32, t, lhi));
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[dt], 0, 0, 0);
+        }
       }
     }
   }
-  const float ltot = psum + __shfl_xor(psum, 32, 64);
+  // row HD of O^T sits in accumulator entry (HD % 32 / 8) * 4 of the last tile, in the lanes with lhi == 0
+  const float ltot = ONES ? __shfl(o[DT - 1][(HD % 32 / 8) * 4], l32, 64) : psum + __shfl_xor(psum, 32, 64);
   const float inv = 1.0f / ltot;
   // A lane holds one query's output in 8-byte pieces 2304 bytes apart from its neighbour's: the wave re-lays its
   // 32 x HD tile through its own piece of LDS and stores whole 16-byte chunks, a query's HD values contiguous.
@@ -750,11 +761,13 @@ Error launch_hd(const void* qkv, void* out, int64_t ldo, int rows, int T, int H,
     constexpr size_t smem_w = whole_lds_bytes(HD, whole_stages_output(HD));
     static bool attr_w = false;
     if (smem_w > 64 * 1024 && !attr_w) {
-      SPECA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attention_mfma_whole_kernel<HD>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem_w)));
+      SPECA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attention_mfma_whole_kernel<HD, false>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem_w)));
+      SPECA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attention_mfma_whole_kernel<HD, true>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem_w)));
       attr_w = true;
     }
     const float sl2 = 1.4426950408889634f / sqrtf(static_cast<float>(HD));
-    attention_mfma_whole_kernel<HD><<<dim3(1, H, rows), 512, smem_w, st>>>(static_cast<const uint16_t*>(qkv), static_cast<uint16_t*>(out), ldo, T, H, sl2);
+    if (T == 256) attention_mfma_whole_kernel<HD, true><<<dim3(1, H, rows), 512, smem_w, st>>>(static_cast<const uint16_t*>(qkv), static_cast<uint16_t*>(out), ldo, T, H, sl2);
+    else attention_mfma_whole_kernel<HD, false><<<dim3(1, H, rows), 512, smem_w, st>>>(static_cast<const uint16_t*>(qkv), static_cast<uint16_t*>(out), ldo, T, H, sl2);
     SPECA_HIP(hipGetLastError());
     return ok();
   }
