@@ -202,7 +202,7 @@ def forecast_verify(args, steps, warmup, with_cpu):
                               "note": "2 x 4.7 MB: launch latency, not bandwidth"},
         "verify_stress_shape": {"rows": slots * B, "elems_per_row": T * D, "bytes_per_call": pv["bytes"] / 10, "achieved_GBps": stress,
                                 "frac": stress / PEAK_HBM_GBPS, "avg_call_us": 1e3 * pv["ms"] / 10,
-                                "note": "224 rows x 294912 bf16 elements, prediction and truth read once: 264 MB per call (four 64-row launches + their final kernels)"},
+                                "note": "224 rows x 294912 bf16 elements, prediction and truth read once: 264 MB per call (one partial-sum launch + one final kernel)"},
         "accepted": [bool(a) for a in acc], "errors": [float(e) for e in err], "cpu": cpu,
     }
     ctx.close()
