@@ -108,6 +108,28 @@ def test_attention(rows, T, H, hd, dtype):
     assert np.max(np.abs(got - exp)) <= (2e-5 if dtype == "f32" else 1.2e-2) * scale
 
 
+@pytest.mark.parametrize("T,hd", [(256, 72), (200, 72), (96, 64)])
+def test_attention_short_sequence_into_an_output_at_8_byte_alignment(T, hd):
+    """The whole-sequence kernel (T <= 256) stores 16-byte chunks; an output that is only 8-byte aligned takes the tiled
+    kernel instead.  Same values either way."""
+    bd = _bd()
+    rows, H = 3, 4
+    rng = np.random.default_rng(7 * T + hd)
+    qkv = si._store(rng.standard_normal((rows, T, 3, H, hd)).astype(np.float32), "bf16")
+    dq = _dev(qkv.reshape(rows, T, 3 * H * hd), "bf16")
+    aligned = bd.attention(dq, H)
+    pool = torch.zeros(rows * T * H * hd + 4, dtype=torch.bfloat16, device="cuda")
+    shifted = pool[4:].view(rows, T, H * hd)                   # data pointer 8 bytes past a 16-byte boundary
+    assert shifted.data_ptr() % 16 == 8
+    bd.attention(dq, H, out=shifted)
+    q, k, v = (qkv[:, :, i].transpose(0, 2, 1, 3).astype(np.float64) for i in range(3))
+    exp = odit.attention(q, k, v).transpose(0, 2, 1, 3).reshape(rows, T, H * hd)
+    scale = np.max(np.abs(exp))
+    for got in (aligned, shifted):
+        assert np.max(np.abs(got.float().cpu().numpy().astype(np.float64) - exp)) <= 1.2e-2 * scale
+    assert float(pool[:4].abs().max()) == 0.0                  # nothing written in front of the output
+
+
 @pytest.mark.parametrize("M,N,K,act", [(27286, 3072, 3072, 0), (27286, 12288, 3072, 1), (4608, 3072, 12288, 0), (4608, 15360 // 5 * 3, 3072, 0)])
 def test_linear_at_mmdit_sizes_sampled_rows(M, N, K, act):
     """The linear layers at the row counts of configurations 4 and 5 (4608 / 27286 tokens, hidden 3072, MLP 12288):
