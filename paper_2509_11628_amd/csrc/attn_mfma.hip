@@ -682,6 +682,17 @@ __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_
   for (int i = 0; i < DT; ++i)
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[i][e] = 0.0f;
+  // V^T fragment addresses: chunk (2t + h) ^ swz(d) = 16 (t >> 3) + ((2 (t & 7)) ^ (h ^ swz(d))) because swz < 16 and h < 2,
+  // so eight per-lane offsets per 32-row tile (one for each t & 7) and an immediate for t >> 3 replace the arithmetic per read
+  // (24 registers at head_dim 72; at head_dim 128 the table would spill, so the offsets are formed per read there)
+  constexpr bool VTAB = DT <= 3;
+  int vto[VTAB ? DT : 1][8];
+#pragma unroll
+  for (int dt = 0; dt < (VTAB ? DT : 0); ++dt) {
+    const int dd = dt * 32 + l32, y = lhi ^ vt_swz<TMAX>(dd);
+#pragma unroll
+    for (int b = 0; b < 8; ++b) vto[dt][b] = dd * TMAX + (((2 * b) ^ y) << 3);
+  }
   // the exponentials of sub-tile st + 1 are issued with the second contraction of sub-tile st
   if (0 < nst) exps(0);
 #pragma unroll
@@ -697,7 +708,7 @@ __global__ __launch_bounds__(512) void attention_mfma_whole_kernel(const uint16_
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
           Frag vf;
-          vf.u = *reinterpret_cast<const uint4*>(Vt + vt_read_off<TMAX>(dt * 32 + l32, t, lhi));
+          vf.u = *reinterpret_cast<const uint4*>(Vt + (VTAB ? vto[VTAB ? dt : 0][t & 7] + (t >> 3) * 128 : vt_read_off<TMAX>(dt * 32 + l32, t, lhi)));
           o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[dt], 0, 0, 0);
         }
       }
