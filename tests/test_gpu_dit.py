@@ -198,6 +198,26 @@ def test_config1_trajectory(tiny):
     assert (tr.kind == 1).sum() > 0 and (tr.kind == 2).sum() > 0     # both paths exercised
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_odd_token_count_trajectory(dtype):
+    """A 6x6 latent gives 9 tokens per row: half a row is not a whole number of tokens, so the forecast-and-fold kernel
+    takes its one-position form, and every tile of the step is ragged.  Guided pairs, order 2, both cache layouts."""
+    s = si.DiTShape(depth=2, hidden=64, heads=4, mlp_hidden=256, in_channels=4, latent_hw=6, patch=2, num_classes=10, freq_dim=32, dtype=dtype)
+    assert s.tokens == 9
+    w = si.make_dit_weights(s, 3)
+    om, ctx = odit.DiTOracle(s, w), make_gpu(s, w)
+    tau = core.tau_geometric(0.3, 0.2, 12)
+    for layout in ("differences", "ring"):
+        exp, tr, got, gtr = _run_both(s, om, ctx, 12, 3, dict(order=2, interval=4, cache_layout=layout), tau, cfg_scale=1.5, seed=2)
+        print(f"\n[{dtype}, {layout}] min decision margin {_margin(tr):.3e}; kinds {tr.kind.tolist()}")
+        compared, complete = compare_traces(tr, gtr, dtype)
+        assert compared >= 6 and (tr.kind == 1).sum() > 0
+        if must_complete(tr, dtype):
+            assert complete
+        if complete:
+            assert max_abs_rel(got, exp) <= _tol(s)
+
+
 def test_config1_geometric_and_newton(tiny):
     s, w, om, ctx = tiny
     tau = core.tau_geometric(0.05, 0.2, 20)
