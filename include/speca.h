@@ -274,7 +274,7 @@ typedef struct speca_profile {
 /* Lanes (an execution option, not part of the method; Sec. 3.2's steps are computed per sample, so
  * the rows of a launch are independent).  A step runs its rows in up to `lanes` groups side by side
  * on library-owned streams forked from and joined to the context's stream with events, so callers
- * see the usual stream order and bit-identical results.  Default 2 (SPECA_LANES in the environment
+ * see the usual stream order and bit-identical results.  Default 4 (SPECA_LANES in the environment
  * at create overrides), 1 = strictly serial, at most 4.  While a profile is open steps run serially
  * (per-kernel event times are only meaningful without overlap) unless profile_keeps_lanes != 0.
  * Returns SPECA_EINVAL for a value outside 1..4. */

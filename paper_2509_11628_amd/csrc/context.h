@@ -47,7 +47,7 @@ struct speca_ctx {
   // on streams of its own (lane 0 is `stream`).  While one group sits in an HBM-bound epilogue or
   // LayerNorm the other keeps the matrix cores busy, and two half-size GEMMs together fill the CUs
   // that one tile-quantised launch leaves idle.  Fork / join with events; results do not change.
-  int lanes = 2;
+  int lanes = 4;
   hipStream_t lane_stream[speca::kMaxLanes] = {};   // [0] = stream; others library-owned
   hipEvent_t lane_fork = nullptr;
   hipEvent_t lane_join[speca::kMaxLanes] = {};
